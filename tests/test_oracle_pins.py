@@ -1,0 +1,362 @@
+"""Pins for the CPU oracle: each part of it is checked against something other
+than itself - the paper's closed forms (Section 2.2, Section 3.2.2), brute
+force on tiny inputs, numpy's int64 matmul as an independent library routine,
+invariants, hand-worked fixtures under tests/golden/, and a host emulation of
+the paper's Algorithm 1.  All of this runs without a GPU.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2305_02522_amd import workloads as W
+from tests import alg1_emulator as alg1
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _bits_of(v):          # +-1 vector -> python int, bit k = (v[k] == +1)
+    x = 0
+    for k, e in enumerate(v):
+        if e > 0:
+            x |= 1 << k
+    return x
+
+
+def _popc(x):
+    return bin(x).count("1")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- BIN
+def test_bin_sign_rule_ties_and_tau():
+    x = np.array([[0.0, -0.0, 1e-30, -1e-30, 3.5, -2.0, np.nan]], dtype=np.float32)
+    v = orc.bin_f32(x)
+    assert v.tolist() == [[1, 1, 1, -1, 1, -1, -1]]
+    tau = np.array([0.5, -1, 0, 0, 3.5, -2.0, 0], dtype=np.float32)
+    v = orc.bin_f32(x, tau)
+    assert v.tolist() == [[-1, 1, 1, -1, 1, 1, -1]]
+    assert orc.bin_i8(np.array([[0, -1, 1, -128, 127]], dtype=np.int8)).tolist() == \
+        [[1, -1, 1, -1, 1]]
+
+
+# ---------------------------------------------------------------- BMM
+def test_bmm_golden_pm1_dot():
+    for line in open(os.path.join(GOLDEN, "pm1_dot.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        a, b, n, pc, c = line.split()
+        va = np.array([[1 if ch == "1" else -1 for ch in a]], dtype=np.int8)
+        vb = np.array([[1 if ch == "1" else -1 for ch in b]], dtype=np.int8).T
+        assert len(a) == int(n)
+        assert _popc(int(a, 2) ^ int(b, 2)) == int(pc)
+        assert orc.bmm(va, vb)[0, 0] == int(c)
+
+
+def test_bmm_exhaustive_small_k_vs_xor_popc():
+    # all 2^K x 2^K pairs: Z = K - 2 popc(x xor w) = 2 popc(xnor) - K
+    for K in (1, 2, 3, 5, 7):
+        allv = np.array(list(itertools.product((-1, 1), repeat=K)), dtype=np.int8)
+        z = orc.bmm(allv, allv.T.copy())
+        ints = [_bits_of(v) for v in allv]
+        full = (1 << K) - 1
+        for i, xi in enumerate(ints):
+            for j, wj in enumerate(ints):
+                assert z[i, j] == K - 2 * _popc(xi ^ wj)
+                assert z[i, j] == 2 * _popc(~(xi ^ wj) & full) - K
+
+
+@pytest.mark.parametrize("K", [1, 63, 64, 65, 100, 602, 1433])
+def test_bmm_random_vs_identity_and_numpy(K):
+    r = _rng(K)
+    x = W.pm1(r, (37, K))
+    w = W.pm1(r, (K, 11))
+    z = orc.bmm(x, w)
+    assert np.array_equal(z, x.astype(np.int64) @ w.astype(np.int64))
+    for i in (0, 17, 36):
+        for c in (0, 5, 10):
+            assert z[i, c] == K - 2 * _popc(_bits_of(x[i]) ^ _bits_of(w[:, c]))
+    assert np.all((z - K) % 2 == 0) and np.all(np.abs(z) <= K)
+
+
+def test_bmm_special_cases():
+    r = _rng(3)
+    x = W.pm1(r, (9, 130))
+    z = orc.bmm(x, x.T.copy())
+    assert np.all(np.diag(z) == 130)              # x = w  -> K
+    z = orc.bmm(x, (-x).T.copy())
+    assert np.all(np.diag(z) == -130)             # x = -w -> -K
+    # not symmetric in shape: a transposed weight operand must fail this
+    w = W.pm1(r, (130, 4))
+    assert orc.bmm(x, w).shape == (9, 4)
+
+
+# ---------------------------------------------------------------- adjacency
+def test_adjacency_set_semantics_and_degree_invariants():
+    r = _rng(11)
+    n = 50
+    src, dst = W.random_graph(r, n, 400)
+    rp, col = orc.adjacency(src, dst, n, 0)
+    pairs = set(zip(src.tolist(), dst.tolist()))
+    got = {(i, int(j)) for i in range(n) for j in col[rp[i]:rp[i + 1]]}
+    assert got == pairs and rp[-1] == len(pairs)
+    for i in range(n):                            # sorted, no duplicates
+        assert np.all(np.diff(col[rp[i]:rp[i + 1]]) > 0)
+    # symmetrise: in-degree == out-degree, membership symmetric
+    rp2, col2 = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE)
+    got2 = {(i, int(j)) for i in range(n) for j in col2[rp2[i]:rp2[i + 1]]}
+    assert got2 == pairs | {(b, a) for a, b in pairs}
+    indeg = np.bincount(col2, minlength=n)
+    assert np.array_equal(indeg, orc.degrees(rp2))
+    # + I: every degree >= 1, nnz grows by N - existing loops
+    rp3, col3 = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    loops = sum(1 for a, b in got2 if a == b)
+    assert rp3[-1] == rp2[-1] + n - loops
+    assert orc.degrees(rp3).min() >= 1 and orc.degrees(rp3).sum() == rp3[-1]
+    # idempotent under duplicate injection and shuffling
+    perm = r.permutation(2 * len(src))
+    s2 = np.concatenate([src, src])[perm]
+    d2 = np.concatenate([dst, dst])[perm]
+    rp4, col4 = orc.adjacency(s2, d2, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    assert np.array_equal(rp3, rp4) and np.array_equal(col3, col4)
+    with pytest.raises(ValueError):
+        orc.adjacency(np.array([0, n]), np.array([0, 0]), n, 0)
+
+
+# ---------------------------------------------------------------- bit-SpMM
+def test_spmm_golden_trinary():
+    for line in open(os.path.join(GOLDEN, "trinary_dot.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        a, b, pab, panb, pa, dot = line.split()
+        n = len(a)
+        ai, bi = int(a, 2), int(b, 2)
+        full = (1 << n) - 1
+        assert _popc(ai & bi) == int(pab) and _popc(ai & ~bi & full) == int(panb)
+        assert _popc(ai) == int(pa)
+        # one aggregating row (node 0) whose neighbours are the set bits of a
+        nbrs = [j for j, ch in enumerate(a) if ch == "1"]
+        rp = np.array([0, len(nbrs)] + [len(nbrs)] * (n - 1), dtype=np.int64)
+        col = np.array(nbrs, dtype=np.int32)
+        v = np.array([[1 if ch == "1" else -1] for ch in b], dtype=np.int8)
+        s = orc.spmm_pm1(rp, col, v)
+        assert s[0, 0] == int(dot)
+        assert int(pab) - int(panb) == int(dot) == 2 * int(pab) - int(pa)
+
+
+def test_spmm_bruteforce_all_graphs_n3():
+    # every 3x3 0/1 adjacency (512 of them) against a fixed +-1 matrix
+    v = np.array([[1, -1, 1, 1], [-1, -1, 1, -1], [1, 1, -1, -1]], dtype=np.int8)
+    for code in range(512):
+        a = np.array([(code >> b) & 1 for b in range(9)], dtype=np.int64).reshape(3, 3)
+        src, dst = np.nonzero(a)
+        rp, col = orc.adjacency(src, dst, 3, 0)
+        assert np.array_equal(orc.spmm_pm1(rp, col, v), a @ v.astype(np.int64))
+
+
+def test_spmm_three_trinary_methods_and_dense_matmul():
+    r = _rng(5)
+    n, c = 64, 70
+    src, dst = W.random_graph(r, n, 600)
+    rp, col = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    v = W.pm1(r, (n, c))
+    s = orc.spmm_pm1(rp, col, v)
+    dense = np.zeros((n, n), dtype=np.int64)
+    for i in range(n):
+        dense[i, col[rp[i]:rp[i + 1]]] = 1
+    assert np.array_equal(s, dense @ v.astype(np.int64))
+    deg = orc.degrees(rp)
+    for i in (0, 13, 63):
+        a = sum(1 << int(j) for j in col[rp[i]:rp[i + 1]])
+        for ch in (0, 31, 69):
+            b = sum(1 << j for j in range(n) if v[j, ch] > 0)
+            full = (1 << n) - 1
+            m2 = _popc(a & b) - _popc(a & ~b & full)
+            m3 = 2 * _popc(a & b) - _popc(a)
+            assert s[i, ch] == m2 == m3
+    # invariants
+    assert np.all((s - deg[:, None]) % 2 == 0) and np.all(np.abs(s) <= deg[:, None])
+    assert np.array_equal(s.sum(axis=0), (deg[:, None] * v).sum(axis=0))  # symmetric A
+    assert np.array_equal(orc.spmm_pm1(rp, col, np.ones_like(v)), np.tile(deg[:, None], (1, c)))
+    assert np.array_equal(orc.spmm_pm1(rp, col, -np.ones_like(v)), -np.tile(deg[:, None], (1, c)))
+    # row-range form returns the same rows
+    assert np.array_equal(orc.spmm_pm1(rp, col, v, (10, 33)), s[10:33])
+
+
+def test_spmm_direction_row_aggregates_columns():
+    # directed 2-node graph: only A[0][1] = 1.  Row 0 must receive v[1].
+    rp, col = orc.adjacency(np.array([0]), np.array([1]), 2, 0)
+    v = np.array([[1, 1], [-1, 1]], dtype=np.int8)
+    assert orc.spmm_pm1(rp, col, v).tolist() == [[-1, 1], [0, 0]]
+    z = np.array([[5, 7], [11, -3]], dtype=np.int64)
+    assert orc.spmm_i64(rp, col, z).tolist() == [[11, -3], [0, 0]]
+
+
+# ---------------------------------------------------------------- threshold
+def test_rebin_threshold_properties():
+    r = _rng(8)
+    acc = r.integers(-9, 10, size=(40, 6)).astype(np.int64)
+    zero = np.zeros(6, dtype=np.int32)
+    assert np.array_equal(orc.rebin(acc, zero), np.where(acc >= 0, 1, -1))
+    prev = None
+    for t in range(-10, 12):
+        v = orc.rebin(acc, np.full(6, t, dtype=np.int32))
+        if prev is not None:
+            assert np.all(v <= prev)              # monotone in T
+        prev = v
+    assert np.all(orc.rebin(acc, np.full(6, -9, dtype=np.int32)) == 1)
+    assert np.all(orc.rebin(acc, np.full(6, 10, dtype=np.int32)) == -1)
+    t = np.array([-4, -1, 0, 1, 2, 4], dtype=np.int32)   # per channel, tie -> +1
+    assert np.array_equal(orc.rebin(acc, t), np.where(acc >= t[None, :], 1, -1))
+
+
+def test_words_roundtrip_and_pad_bits():
+    r = _rng(2)
+    for k in (1, 63, 64, 65, 130):
+        v = W.pm1(r, (5, k))
+        words = orc.to_words(v)
+        assert words.shape == (5, (k + 63) // 64)
+        assert np.array_equal(orc.from_words(words, k), v)
+        for i in range(5):
+            x = sum(int(words[i, w]) << (64 * w) for w in range(words.shape[1]))
+            assert x == _bits_of(v[i])            # bit k%64 of word k//64, pad bits 0
+
+
+# ---------------------------------------------------------------- last layer
+def test_last_layer_associativity_and_scale():
+    r = _rng(21)
+    n, k, m = 80, 33, 5
+    src, dst = W.random_graph(r, n, 500)
+    rp, col = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    h = W.pm1(r, (n, k))
+    w = W.pm1(r, (k, m))
+    y = orc.spmm_i64(rp, col, orc.bmm(h, w))                   # A (H W)
+    y2 = orc.spmm_pm1(rp, col, h) @ w.astype(np.int64)         # (A H) W
+    assert np.array_equal(y, y2)
+    ones = np.ones(m, dtype=np.float32)
+    assert np.array_equal(orc.scale(y, ones), y.astype(np.float32))
+    alpha = r.uniform(0.5, 1.5, m).astype(np.float32)
+    out = orc.gcn_out_layer(rp, col, h, w, alpha)
+    assert np.allclose(out, alpha.astype(np.float64) * y, rtol=1e-7, atol=0)
+
+
+# ---------------------------------------------------------------- whole models
+def _parse_rows(s, dtype=np.int64):
+    return np.array([[float(t) for t in row.split()] for row in s.split("|")]).astype(dtype)
+
+
+def test_gcn_golden_tiny_handworked():
+    f = {}
+    for line in open(os.path.join(GOLDEN, "gcn_tiny.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, rest = line.split(None, 1)
+        f[key] = rest.strip()
+    n = int(f["n"])
+    e = [tuple(map(int, p.split("-"))) for p in f["edges"].split()]
+    src = np.array([a for a, _ in e])
+    dst = np.array([b for _, b in e])
+    rp, col = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    x = _parse_rows(f["x"], np.int8)
+    w1 = _parse_rows(f["w1"], np.int8)
+    w2 = _parse_rows(f["w2"], np.int8)
+    t_mm = np.array(f["t_mm"].split(), dtype=np.int32)
+    t_agg = np.array(f["t_agg"].split(), dtype=np.int32)
+    z1 = orc.bmm(x, w1)
+    assert np.array_equal(z1, _parse_rows(f["z1"]))
+    h = orc.rebin(z1, t_mm)
+    assert np.array_equal(h, _parse_rows(f["h"]))
+    s = orc.spmm_pm1(rp, col, h)
+    assert np.array_equal(s, _parse_rows(f["s"]))
+    out1 = orc.rebin(s, t_agg)
+    assert np.array_equal(out1, _parse_rows(f["out1"]))
+    assert np.array_equal(orc.gcn_hidden_layer(rp, col, x, w1, t_mm, t_agg), out1)
+    z2 = orc.bmm(out1, w2)
+    assert np.array_equal(z2, _parse_rows(f["z2"]))
+    assert np.array_equal(orc.spmm_i64(rp, col, z2), _parse_rows(f["y"]))
+    alpha = np.array([float(f["alpha"])], dtype=np.float32)
+    logits = orc.gcn_out_layer(rp, col, out1, w2, alpha)
+    assert np.array_equal(logits, _parse_rows(f["logits"], np.float32))
+
+
+def _dense_adj(n, rp, col):
+    a = np.zeros((n, n), dtype=np.int64)
+    for i in range(n):
+        a[i, col[rp[i]:rp[i + 1]]] = 1
+    return a
+
+
+def test_config1_gcn_vs_dense_textbook_evaluation():
+    wl = W.make_workload(1)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    nnz_no_loops = rp[-1] - wl.n
+    assert 9000 < nnz_no_loops < 12000            # ~10.5k stored non-zeros + N loops
+    a = _dense_adj(wl.n, rp, col)
+    assert np.array_equal(a, a.T) and np.all(np.diag(a) == 1)
+    logits, hidden = orc.forward("gcn", rp, col, wl.x, wl.layers, return_hidden=True)
+    l1, l2 = wl.layers
+    x = wl.x.astype(np.int64)
+    h = np.where(x @ l1.w.astype(np.int64) >= l1.t_mm[None, :], 1, -1)
+    out1 = np.where(a @ h >= l1.t_agg[None, :], 1, -1)
+    assert np.array_equal(hidden[0], out1)
+    y = a @ (out1 @ l2.w.astype(np.int64))
+    ref = l2.alpha.astype(np.float64)[None, :] * y
+    assert np.allclose(logits, ref, rtol=1e-6, atol=0)
+    assert logits.dtype == np.float32 and logits.shape == (wl.n, 7)
+
+
+def test_sage_small_vs_two_matmul_form():
+    # [self | nbr] [W1; W2] == self W1 + nbr W2 (GraphConv sum form), no self loops
+    wl = W.make_workload(3, n=700)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    a = _dense_adj(wl.n, rp, col)
+    assert np.all(np.diag(a) == 0) and np.array_equal(a, a.T)
+    logits, hidden = orc.forward("sage", rp, col, wl.x, wl.layers, return_hidden=True)
+    v = wl.x.astype(np.int64)
+    for l, p in enumerate(wl.layers):
+        k_in = v.shape[1]
+        nb = np.where(a @ v >= p.t_agg[None, :], 1, -1)
+        z = v @ p.w[:k_in].astype(np.int64) + nb @ p.w[k_in:].astype(np.int64)
+        if p.alpha is None:
+            v = np.where(z >= p.t_mm[None, :], 1, -1)
+            assert np.array_equal(hidden[l], v)
+        else:
+            assert np.allclose(logits, p.alpha.astype(np.float64)[None, :] * z, rtol=1e-6, atol=0)
+    iso = np.nonzero(orc.degrees(rp) == 0)[0]     # isolated node: S = 0, bit = (0 >= T)
+    if len(iso):
+        nb0 = orc.rebin(orc.spmm_pm1(rp, col, wl.x), wl.layers[0].t_agg)
+        assert np.array_equal(nb0[iso[0]], np.where(0 >= wl.layers[0].t_agg, 1, -1))
+
+
+# ---------------------------------------------------------------- Algorithm 1
+def test_alg1_tile_set_count_example():
+    # Section 3.3.2, steps 1-2: ten tiles make two tile groups of 8 slots
+    assert alg1.TS == 8 and alg1.n_tile_sets(10) == 2 and alg1.n_tile_sets(8) == 1
+
+
+@pytest.mark.parametrize("n,e,c,seed", [(7, 20, 32, 0), (30, 140, 40, 1), (45, 700, 64, 2)])
+def test_alg1_emulator_equals_oracle(n, e, c, seed):
+    r = _rng(seed)
+    src, dst = W.random_graph(r, n, e)
+    rp, col = orc.adjacency(src, dst, n, orc.ADJ_SYMMETRIZE | orc.ADJ_ADD_SELF_LOOPS)
+    v = W.pm1(r, (n, c))
+    n_words = (c + 31) // 32
+    words = [[0] * n_words for _ in range(n)]
+    for j in range(n):
+        for ch in range(c):
+            if v[j, ch] > 0:
+                words[j][ch // 32] |= 1 << (ch % 32)
+    frdc = alg1.build_frdc(n, rp, col)
+    if n == 45:
+        assert max(np.diff(frdc[0])) > alg1.TS        # more than one tile set
+    out = alg1.bspmm_bbb(n, frdc, words, n_words)
+    expect = orc.rebin(orc.spmm_pm1(rp, col, v), np.zeros(c, dtype=np.int32))
+    for i in range(n):
+        for ch in range(c):
+            bit = (out[i][ch // 32] >> (ch % 32)) & 1
+            assert bit == (1 if expect[i, ch] > 0 else 0)
