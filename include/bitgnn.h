@@ -1,0 +1,194 @@
+/*
+ * bitgnn.h - C ABI of the MI355X (gfx950) binary-GNN inference library.
+ *
+ * The calls follow the problem statement of BitGNN (ICS '23): binarize and
+ * bit-pack node features, build the adjacency, run binary GCN / GraphSAGE
+ * layers (bit matrix product for the feature transformation, bit sparse
+ * product for the neighbour aggregation, re-binarization fused into both),
+ * return float logits.
+ *
+ * Conventions for every entry point
+ *  - returns BITGNN_OK (0) or a negative BITGNN_ERR_* code; nothing throws.
+ *    A message for the last failure of a context is kept in the context
+ *    (bitgnn_last_error).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Compute calls only enqueue work on it and return; bitgnn_adj_build
+ *    synchronizes the stream before it returns.  A context serves ONE stream at
+ *    a time: it owns a small device scratch table that concurrent calls would
+ *    race on.
+ *  - every data pointer is a DEVICE pointer owned by the caller and must stay
+ *    valid until the enqueued work has run.  The library allocates device
+ *    memory only inside a context (a few KB) and inside a bitgnn_adj.
+ *  - packed bit layout (part of the ABI): a packed matrix is row-major
+ *    uint64 words, little endian; logical bit k of a row is bit (k % 64) of
+ *    word (k / 64); bit 1 encodes +1 and bit 0 encodes -1.  Rows are addressed
+ *    as (pointer, row stride in words), so a caller can place a packed block at
+ *    any word offset inside a wider row (GraphSAGE's [self | neighbour] rows).
+ *    Bits past the logical width in the last word are ZERO in every output and
+ *    must be zero in every input.
+ *  - a context created with device = -1 has no GPU: every call still validates
+ *    its arguments and then returns BITGNN_ERR_NO_DEVICE instead of launching.
+ *    There is no CPU implementation behind this library.
+ */
+#ifndef BITGNN_H
+#define BITGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bitgnn_ctx bitgnn_ctx; /* opaque, library-owned */
+typedef struct bitgnn_adj bitgnn_adj; /* opaque, library-owned, immutable once built */
+
+enum {
+    BITGNN_OK = 0,
+    BITGNN_ERR_INVALID_ARG = -1, /* null pointer, negative or inconsistent size, bad enum */
+    BITGNN_ERR_ALIGNMENT = -2,   /* pointer not aligned to its element type */
+    BITGNN_ERR_INDEX_RANGE = -3, /* an edge endpoint is outside [0, N) */
+    BITGNN_ERR_RANGE = -4,       /* an int32 accumulator or a 32-bit offset could overflow */
+    BITGNN_ERR_HIP = -5,         /* a HIP runtime call failed (code in the message) */
+    BITGNN_ERR_UNSUPPORTED = -6, /* size beyond what the kernels are built for */
+    BITGNN_ERR_NO_DEVICE = -7    /* arguments are valid but the context has no GPU */
+};
+
+enum {
+    BITGNN_ADJ_SYMMETRIZE = 1,    /* also store (j, i) for every (i, j) */
+    BITGNN_ADJ_ADD_SELF_LOOPS = 2 /* A_hat = A + I (Section 2.1, GCNConv) */
+};
+
+enum {
+    BITGNN_EPI_RAW_I32 = 0,     /* int32 accumulators */
+    BITGNN_EPI_THRESH_BITS = 1, /* bit = (acc >= T[c]), packed */
+    BITGNN_EPI_SCALE_F32 = 2    /* float = alpha[c] * (float)acc */
+};
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Creates a context on HIP device `device` (>= 0), or a GPU-less validation
+ * context (device == -1).  *out is set only on success. */
+int bitgnn_ctx_create(bitgnn_ctx **out, int device);
+void bitgnn_ctx_destroy(bitgnn_ctx *ctx);
+/* Message of the most recent failing call on `ctx` ("" if none).  The string
+ * is owned by the context and valid until the next call on it. */
+const char *bitgnn_last_error(const bitgnn_ctx *ctx);
+
+/* ---- BIN: binarize and pack (Section 2.2 sign rule; Section 2.3) --------- */
+
+/* out[i][k/64] bit k%64 = (x[i*ldx + k] >= tau[k]) for k < K; tau == NULL means
+ * tau = 0, the paper's sign function (x >= 0 -> +1, so -0.0 -> +1; NaN -> -1).
+ * A per-column tau is BatchNorm folded into the comparison.
+ * x: float [n][ldx] (ldx >= K); out: uint64 [n][out_stride], the call writes
+ * ceil(K/64) words of every row and leaves the rest of the row untouched. */
+int bitgnn_pack_f32(bitgnn_ctx *ctx, void *stream, const float *x, int64_t n, int32_t K,
+                    int64_t ldx, const float *tau, uint64_t *out, int64_t out_stride);
+/* Same for int8 input with the fixed rule x >= 0 -> bit 1. */
+int bitgnn_pack_i8(bitgnn_ctx *ctx, void *stream, const int8_t *x, int64_t n, int32_t K,
+                   int64_t ldx, uint64_t *out, int64_t out_stride);
+/* Packs a weight matrix transposed, as the BGEMM wants it (weights are
+ * binarized offline, Section 3.1.1): out[c][k/64] bit k%64 = (w[k*ldw + c] >= 0)
+ * for k < K, c < M.  w: int8 [K][ldw]; out: uint64 [M][out_stride]. */
+int bitgnn_pack_weights_i8(bitgnn_ctx *ctx, void *stream, const int8_t *w, int32_t K, int32_t M,
+                           int64_t ldw, uint64_t *out, int64_t out_stride);
+
+/* ---- adjacency (Section 2.1 A_hat; Section 3.2.1 sparse bit representation) */
+
+/* Builds the 0/1 aggregation matrix from an edge list: A_hat[i][j] = 1 iff
+ * (src, dst) = (i, j) occurs (or (j, i) with SYMMETRIZE, or i == j with
+ * ADD_SELF_LOOPS).  Duplicates collapse (set semantics).  Row i of the result
+ * lists N(i) = { j : A_hat[i][j] = 1 } in increasing j.
+ * src, dst: int32 [E] device arrays, left unchanged.  Requires
+ * E*(1 + symmetrize) + N < 2^31.  Synchronizes `stream`.  Temporary sort
+ * buffers are freed before returning; the handle keeps the CSR arrays, the
+ * degrees and a degree-sorted row order.
+ * Errors: BITGNN_ERR_INDEX_RANGE if an endpoint is outside [0, N). */
+int bitgnn_adj_build(bitgnn_ctx *ctx, void *stream, const int32_t *src, const int32_t *dst,
+                     int64_t E, int64_t N, uint32_t flags, bitgnn_adj **out);
+/* Any output pointer may be NULL. */
+int bitgnn_adj_info(const bitgnn_adj *adj, int64_t *N, int64_t *nnz, int64_t *max_degree,
+                    size_t *device_bytes);
+/* Device views of the handle's arrays (owned by the handle): rowptr uint32
+ * [N+1], col int32 [nnz] (sorted inside each row), deg int32 [N]. */
+int bitgnn_adj_csr(const bitgnn_adj *adj, const uint32_t **rowptr, const int32_t **col,
+                   const int32_t **deg);
+void bitgnn_adj_destroy(bitgnn_adj *adj);
+
+/* ---- BMM: XNOR-popcount product (Section 2.2, +-1 bit-dot-product) ------- */
+
+/* Z[i][c] = sum_k vx[i][k]*vw[k][c] = K - 2*popc(xbits_i xor wbits_c), where the
+ * xor runs over `kwords` words of both operands and K is the number of logical
+ * (non-pad) bits among them (pad bits are zero in both, so they cancel).
+ * xbits: uint64 [n][x_stride]; wbits: uint64 [M][w_stride] (K along the bits).
+ * epilogue RAW_I32:     out = int32 [n][out_stride] <- Z
+ *          THRESH_BITS: out = uint64 [n][out_stride], ceil(M/64) words per row
+ *                       <- bit c = (Z >= T[c]); needs T (int32 [M])
+ *          SCALE_F32:   out = float [n][out_stride] <- alpha[c]*(float)Z; needs
+ *                       alpha (float [M])
+ * Covers the BMM.BBB / BMM.BBF variants of Section 3.1.2 (BIN and SCL folded
+ * in; a scale before a re-binarization is dropped because it is positive). */
+int bitgnn_bgemm(bitgnn_ctx *ctx, void *stream, const uint64_t *xbits, int64_t n,
+                 int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits, int32_t M,
+                 int64_t w_stride, int epilogue, const int32_t *T, const float *alpha, void *out,
+                 int64_t out_stride);
+
+/* ---- BSpMM: bit sparse product (Section 3.2.2; Algorithm 1) -------------- */
+
+/* S[i][c] = sum_{j in N(i)} v[j][c] = 2*#{j in N(i) : bit c of hbits_j} - deg(i)
+ * (trinary 0/1 x +-1 dot product, method 3) for c < C.
+ * hbits: uint64 [N][h_stride].
+ * epilogue RAW_I32:     out = int32 [N][out_stride] <- S
+ *          THRESH_BITS: out = uint64 [N][out_stride], ceil(C/64) words per row
+ *                       <- bit c = (S >= T[c]) (Algorithm 1's c >= 0 with the
+ *                       BatchNorm threshold in place of 0); needs T (int32 [C]).
+ * `out` may lie in the same rows as hbits as long as the words do not overlap. */
+int bitgnn_bspmm(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const uint64_t *hbits,
+                 int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
+                 int64_t out_stride);
+
+/* Aggregation of integer activations over the 0/1 adjacency (the last layer's
+ * BSpMM.FBF of the binary-aggregation model, kept in exact integers):
+ * Y[i][c] = sum_{j in N(i)} Z[j][c], c < M.  Z: int32 [N][z_stride].
+ * alpha != NULL: out = float [N][out_stride] <- alpha[c]*(float)Y
+ * alpha == NULL: out = int32 [N][out_stride] <- Y
+ * z_abs_bound: the caller's bound on |Z| (e.g. K); the call fails with
+ * BITGNN_ERR_RANGE if max_degree * z_abs_bound >= 2^31. */
+int bitgnn_spmm_i32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const int32_t *Z,
+                    int32_t M, int64_t z_stride, int64_t z_abs_bound, const float *alpha,
+                    void *out, int64_t out_stride);
+
+/* ---- layers (Section 3.1.2 high-level functions; Table 3 caption recipe) - */
+
+/* GCN hidden layer, BMM.xBB + BSpMM.BBB:
+ *   h = (xbits W >= T_mm) ; out = (A_hat h >= T_agg).
+ * tmp_bits: caller scratch uint64 [N][ceil(M/64)] for h. */
+int bitgnn_gcn_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const uint64_t *xbits,
+                     int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits,
+                     int32_t M, int64_t w_stride, const int32_t *T_mm, const int32_t *T_agg,
+                     uint64_t *tmp_bits, uint64_t *out_bits, int64_t out_stride);
+/* GCN output layer, BMM.BBF + BSpMM.FBF with one scale at the end:
+ *   logits = alpha * (A_hat (xbits W)).  tmp_i32: caller scratch int32 [N][M]. */
+int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                         const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
+                         const uint64_t *wbits, int32_t M, int64_t w_stride, const float *alpha,
+                         int32_t *tmp_i32, float *logits, int64_t ldo);
+/* GraphSAGE / GraphConv hidden layer in concatenated form (sum aggregation,
+ * Section 2.1):  nb = (A self >= T_agg) ; out = ([self | nb] W >= T_mm).
+ * cat_bits: uint64 [N][2*kw] with kw = ceil(K_in/64); words [0, kw) of a row
+ * hold the node's own bits on entry, words [kw, 2kw) receive nb.  wbits is
+ * [M][2*kw] laid out the same way (K = 2*K_in logical bits). */
+int bitgnn_sage_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, uint64_t *cat_bits,
+                      int32_t K_in, const uint64_t *wbits, int32_t M, int64_t w_stride,
+                      const int32_t *T_agg, const int32_t *T_mm, uint64_t *out_bits,
+                      int64_t out_stride);
+/* GraphSAGE output layer: logits = alpha * ([self | nb] W). */
+int bitgnn_sage_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                          uint64_t *cat_bits, int32_t K_in, const uint64_t *wbits, int32_t M,
+                          int64_t w_stride, const int32_t *T_agg, const float *alpha,
+                          float *logits, int64_t ldo);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITGNN_H */

@@ -1,0 +1,302 @@
+"""ctypes binding of libbitgnn.so: same entry points as include/bitgnn.h, argument
+marshalling only.  torch tensors provide device memory and the stream; every
+step of the computation runs in the library's HIP kernels.  There is no CPU
+path: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbitgnn.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_ALIGNMENT = -2
+ERR_INDEX_RANGE = -3
+ERR_RANGE = -4
+ERR_HIP = -5
+ERR_UNSUPPORTED = -6
+ERR_NO_DEVICE = -7
+
+ADJ_SYMMETRIZE = 1
+ADJ_ADD_SELF_LOOPS = 2
+
+EPI_RAW_I32 = 0
+EPI_THRESH_BITS = 1
+EPI_SCALE_F32 = 2
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} not found: build it with `python -m paper_2305_02522_amd.build` "
+        "(there is no fallback implementation)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _i32, _u32, _int = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32,
+                               ctypes.c_int)
+
+_SIGNATURES = {
+    "bitgnn_ctx_create": (_int, [ctypes.POINTER(_vp), _int]),
+    "bitgnn_ctx_destroy": (None, [_vp]),
+    "bitgnn_last_error": (ctypes.c_char_p, [_vp]),
+    "bitgnn_pack_f32": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _vp, _i64]),
+    "bitgnn_pack_i8": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _i64]),
+    "bitgnn_pack_weights_i8": (_int, [_vp, _vp, _vp, _i32, _i32, _i64, _vp, _i64]),
+    "bitgnn_adj_build": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _u32, ctypes.POINTER(_vp)]),
+    "bitgnn_adj_info": (_int, [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64),
+                               ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_size_t)]),
+    "bitgnn_adj_csr": (_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]),
+    "bitgnn_adj_destroy": (None, [_vp]),
+    "bitgnn_bgemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _i32, _i64, _int, _vp,
+                            _vp, _vp, _i64]),
+    "bitgnn_bspmm": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
+    "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
+    "bitgnn_gcn_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp, _vp,
+                                _vp, _vp, _i64]),
+    "bitgnn_gcn_out_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp,
+                                    _vp, _vp, _i64]),
+    "bitgnn_sage_layer": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp, _vp, _i64]),
+    "bitgnn_sage_out_layer": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp, _vp,
+                                     _i64]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+for _name, (_res, _args) in _SIGNATURES.items():
+    _fn = getattr(_lib, _name)      # AttributeError if the library lacks a declared symbol
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+class BitgnnError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"bitgnn error {code}: {message}")
+        self.code = code
+
+
+def _ptr(t):
+    """Device address of a tensor (or a raw int address, or None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    if torch.cuda.is_available():
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+class Context:
+    """bitgnn_ctx.  device=-1 gives the GPU-less validation context."""
+
+    def __init__(self, device: int = 0):
+        h = _vp()
+        rc = _lib.bitgnn_ctx_create(ctypes.byref(h), device)
+        if rc != OK:
+            raise BitgnnError(rc, "bitgnn_ctx_create failed")
+        self.handle = h
+        self.device = device
+
+    def close(self):
+        if self.handle:
+            _lib.bitgnn_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return _lib.bitgnn_last_error(self.handle).decode()
+
+    def check(self, rc: int):
+        if rc != OK:
+            raise BitgnnError(rc, self.last_error())
+
+
+class Adjacency:
+    """bitgnn_adj handle (device arrays owned by the library)."""
+
+    def __init__(self, handle):
+        self.handle = handle
+        n, nnz, md, nb = _i64(), _i64(), _i64(), ctypes.c_size_t()
+        _lib.bitgnn_adj_info(handle, ctypes.byref(n), ctypes.byref(nnz), ctypes.byref(md),
+                             ctypes.byref(nb))
+        self.n, self.nnz, self.max_degree, self.device_bytes = n.value, nnz.value, md.value, nb.value
+
+    def csr_pointers(self):
+        rp, col, deg = _vp(), _vp(), _vp()
+        _lib.bitgnn_adj_csr(self.handle, ctypes.byref(rp), ctypes.byref(col), ctypes.byref(deg))
+        return rp.value, col.value, deg.value
+
+    def close(self):
+        if self.handle:
+            _lib.bitgnn_adj_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def words(k: int) -> int:
+    return (k + 63) // 64
+
+
+# --- one function per C entry point ----------------------------------------
+
+def pack_f32(ctx: Context, x, n, K, ldx, tau, out, out_stride):
+    ctx.check(_lib.bitgnn_pack_f32(ctx.handle, _stream(), _ptr(x), n, K, ldx, _ptr(tau), _ptr(out),
+                                   out_stride))
+
+
+def pack_i8(ctx: Context, x, n, K, ldx, out, out_stride):
+    ctx.check(_lib.bitgnn_pack_i8(ctx.handle, _stream(), _ptr(x), n, K, ldx, _ptr(out), out_stride))
+
+
+def pack_weights_i8(ctx: Context, w, K, M, ldw, out, out_stride):
+    ctx.check(_lib.bitgnn_pack_weights_i8(ctx.handle, _stream(), _ptr(w), K, M, ldw, _ptr(out),
+                                          out_stride))
+
+
+def adj_build(ctx: Context, src, dst, E, N, flags) -> Adjacency:
+    h = _vp()
+    ctx.check(_lib.bitgnn_adj_build(ctx.handle, _stream(), _ptr(src), _ptr(dst), E, N, flags,
+                                    ctypes.byref(h)))
+    return Adjacency(h)
+
+
+def bgemm(ctx: Context, xbits, n, x_stride, K, kwords, wbits, M, w_stride, epilogue, T, alpha, out,
+          out_stride):
+    ctx.check(_lib.bitgnn_bgemm(ctx.handle, _stream(), _ptr(xbits), n, x_stride, K, kwords,
+                                _ptr(wbits), M, w_stride, epilogue, _ptr(T), _ptr(alpha), _ptr(out),
+                                out_stride))
+
+
+def bspmm(ctx: Context, adj: Optional[Adjacency], hbits, C, h_stride, epilogue, T, out, out_stride):
+    ctx.check(_lib.bitgnn_bspmm(ctx.handle, _stream(), adj.handle if adj else None, _ptr(hbits), C,
+                                h_stride, epilogue, _ptr(T), _ptr(out), out_stride))
+
+
+def spmm_i32(ctx: Context, adj: Optional[Adjacency], Z, M, z_stride, z_abs_bound, alpha, out,
+             out_stride):
+    ctx.check(_lib.bitgnn_spmm_i32(ctx.handle, _stream(), adj.handle if adj else None, _ptr(Z), M,
+                                   z_stride, z_abs_bound, _ptr(alpha), _ptr(out), out_stride))
+
+
+def gcn_layer(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride, T_mm, T_agg,
+              tmp_bits, out_bits, out_stride):
+    ctx.check(_lib.bitgnn_gcn_layer(ctx.handle, _stream(), adj.handle if adj else None,
+                                    _ptr(xbits), x_stride, K, kwords, _ptr(wbits), M, w_stride,
+                                    _ptr(T_mm), _ptr(T_agg), _ptr(tmp_bits), _ptr(out_bits),
+                                    out_stride))
+
+
+def gcn_out_layer(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride, alpha,
+                  tmp_i32, logits, ldo):
+    ctx.check(_lib.bitgnn_gcn_out_layer(ctx.handle, _stream(), adj.handle if adj else None,
+                                        _ptr(xbits), x_stride, K, kwords, _ptr(wbits), M, w_stride,
+                                        _ptr(alpha), _ptr(tmp_i32), _ptr(logits), ldo))
+
+
+def sage_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg, T_mm, out_bits,
+               out_stride):
+    ctx.check(_lib.bitgnn_sage_layer(ctx.handle, _stream(), adj.handle if adj else None,
+                                     _ptr(cat_bits), K_in, _ptr(wbits), M, w_stride, _ptr(T_agg),
+                                     _ptr(T_mm), _ptr(out_bits), out_stride))
+
+
+def sage_out_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg, alpha, logits,
+                   ldo):
+    ctx.check(_lib.bitgnn_sage_out_layer(ctx.handle, _stream(), adj.handle if adj else None,
+                                         _ptr(cat_bits), K_in, _ptr(wbits), M, w_stride,
+                                         _ptr(T_agg), _ptr(alpha), _ptr(logits), ldo))
+
+
+# --- model runner: buffers + the call sequence, no arithmetic ---------------
+
+class BinaryGNN:
+    """Holds the packed parameters and activation buffers of one model on the GPU
+    and runs the layer calls in order.  `layers` are objects with fields w (int8
+    [K_total, M], +-1), t_mm, t_agg (int32) and alpha (float32, last layer)."""
+
+    def __init__(self, ctx: Context, model: str, adj: Adjacency, dims: Sequence[int],
+                 layers: Sequence, device="cuda"):
+        assert model in ("gcn", "sage")
+        self.ctx, self.model, self.adj, self.dims = ctx, model, adj, list(dims)
+        n = adj.n
+        self.n = n
+        dev = torch.device(device)
+        self.params = []
+        for l, p in enumerate(layers):
+            k_in, m = dims[l], dims[l + 1]
+            kw = words(k_in)
+            w = torch.as_tensor(p.w, dtype=torch.int8, device=dev).contiguous()
+            if model == "gcn":
+                wb = torch.zeros((m, kw), dtype=torch.int64, device=dev)
+                pack_weights_i8(ctx, w, k_in, m, m, wb, kw)
+            else:
+                wb = torch.zeros((m, 2 * kw), dtype=torch.int64, device=dev)
+                pack_weights_i8(ctx, w, k_in, m, m, wb, 2 * kw)
+                pack_weights_i8(ctx, w[k_in:], k_in, m, m, wb[:, kw:], 2 * kw)
+            d = dict(wb=wb, kw=kw, k_in=k_in, m=m)
+            for name, dt in (("t_mm", torch.int32), ("t_agg", torch.int32),
+                             ("alpha", torch.float32)):
+                v = getattr(p, name)
+                d[name] = None if v is None else torch.as_tensor(v, dtype=dt, device=dev)
+            self.params.append(d)
+        # activation buffers: bits entering layer l
+        self.act: List[torch.Tensor] = []
+        for l in range(len(layers)):
+            kw = words(dims[l])
+            width = kw if model == "gcn" else 2 * kw
+            self.act.append(torch.zeros((n, width), dtype=torch.int64, device=dev))
+        m_last = dims[-1]
+        self.logits = torch.empty((n, m_last), dtype=torch.float32, device=dev)
+        if model == "gcn":
+            mw = max(words(d) for d in dims[1:-1]) if len(dims) > 2 else 1
+            self.tmp_bits = torch.zeros((n, mw), dtype=torch.int64, device=dev)
+            self.tmp_i32 = torch.empty((n, m_last), dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+
+    def forward(self, x_f32: torch.Tensor) -> torch.Tensor:
+        """x_f32: float32 [N, K0] on the GPU.  Returns float32 logits [N, classes]."""
+        ctx, adj = self.ctx, self.adj
+        n, k0 = x_f32.shape
+        assert n == self.n and k0 == self.dims[0]
+        a0 = self.act[0]
+        pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
+        nl = len(self.params)
+        for l, p in enumerate(self.params):
+            a = self.act[l]
+            last = l == nl - 1
+            if self.model == "gcn":
+                if last:
+                    gcn_out_layer(ctx, adj, a, a.stride(0), p["k_in"], p["kw"], p["wb"], p["m"],
+                                  p["wb"].stride(0), p["alpha"], self.tmp_i32, self.logits,
+                                  self.logits.stride(0))
+                else:
+                    nxt = self.act[l + 1]
+                    gcn_layer(ctx, adj, a, a.stride(0), p["k_in"], p["kw"], p["wb"], p["m"],
+                              p["wb"].stride(0), p["t_mm"], p["t_agg"], self.tmp_bits, nxt,
+                              nxt.stride(0))
+            else:
+                if last:
+                    sage_out_layer(ctx, adj, a, p["k_in"], p["wb"], p["m"], p["wb"].stride(0),
+                                   p["t_agg"], p["alpha"], self.logits, self.logits.stride(0))
+                else:
+                    nxt = self.act[l + 1]
+                    sage_layer(ctx, adj, a, p["k_in"], p["wb"], p["m"], p["wb"].stride(0),
+                               p["t_agg"], p["t_mm"], nxt, nxt.stride(0))
+        return self.logits

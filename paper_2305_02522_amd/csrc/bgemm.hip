@@ -1,0 +1,182 @@
+// BMM: XNOR-popcount product of bit-packed +-1 activations and weights
+// (Section 2.2: c = n - 2 popc(a xor b)), with the re-binarization or the scale
+// folded into the epilogue (Section 3.1.2, BMM variants).
+//
+// gfx950 mapping (plain VALU; CDNA4 has no 1-bit matrix instruction):
+//  - a lane owns one output channel c; its weight words sit in VGPRs
+//  - a wavefront walks 32 node rows; the activation words of a row are the
+//    same for all 64 lanes, so they are fetched with wave-uniform (scalar)
+//    loads and used as scalar operands of v_xor
+//  - v_bcnt_u32_b32 accumulates the popcount for free (third operand)
+//  - the thresholded output bit of 64 channels is the wave-wide compare mask,
+//    i.e. already the packed output word: no shuffles or votes beyond it
+// The kernel is bound by VALU issue (2 lane-ops per 32 bit-MACs), not by HBM.
+#include "common.h"
+
+namespace {
+
+constexpr int kWaves = 4;  // wavefronts per workgroup
+constexpr int kRows = 32;  // node rows per wavefront
+constexpr int kChunk = 8;  // 32-bit words of the K axis held per step
+
+template <int EPI>
+__global__ __launch_bounds__(kWaves * 64) void bgemm_kernel(
+    const uint32_t *__restrict__ x32, int64_t n, int64_t x_stride32, int32_t K, int32_t kw32,
+    const uint32_t *__restrict__ w32, int32_t M, int64_t w_stride32,
+    const int32_t *__restrict__ T, const float *__restrict__ alpha, void *__restrict__ out,
+    int64_t out_stride)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRows;
+    if (row0 >= n)
+        return;
+    const int ct = blockIdx.y;
+    const int c = ct * 64 + lane;
+    const bool c_ok = c < M;
+    const uint32_t *wrow = w32 + (int64_t)(c_ok ? c : 0) * w_stride32;
+
+    int acc[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r)
+        acc[r] = 0;
+
+    for (int k0 = 0; k0 < kw32; k0 += kChunk) {
+        uint32_t wv[kChunk];
+        if (k0 + kChunk <= kw32) {
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j)
+                wv[j] = wrow[k0 + j];
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                const int64_t row = (row0 + r < n) ? row0 + r : n - 1; // wave-uniform
+                const uint32_t *xr = x32 + row * x_stride32 + k0;
+#pragma unroll
+                for (int j = 0; j < kChunk; ++j)
+                    acc[r] += __popc(xr[j] ^ wv[j]);
+            }
+        } else {
+            const int rem = kw32 - k0; // 1..kChunk-1, wave-uniform
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j)
+                wv[j] = (j < rem) ? wrow[k0 + j] : 0u;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                const int64_t row = (row0 + r < n) ? row0 + r : n - 1;
+                const uint32_t *xr = x32 + row * x_stride32 + k0;
+#pragma unroll
+                for (int j = 0; j < kChunk; ++j)
+                    if (j < rem)
+                        acc[r] += __popc(xr[j] ^ wv[j]);
+            }
+        }
+    }
+
+    if (EPI == BITGNN_EPI_THRESH_BITS) {
+        const int32_t tc = c_ok ? T[c] : 0;
+        uint64_t mine = 0;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const int32_t z = K - 2 * acc[r];
+            const uint64_t m = __ballot(c_ok && z >= tc);
+            if (lane == r)
+                mine = m;
+        }
+        if (lane < kRows && row0 + lane < n)
+            ((uint64_t *)out)[(row0 + lane) * out_stride + ct] = mine;
+    } else if (EPI == BITGNN_EPI_RAW_I32) {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r)
+            if (c_ok && row0 + r < n)
+                ((int32_t *)out)[(row0 + r) * out_stride + c] = K - 2 * acc[r];
+    } else {
+        const float a = c_ok ? alpha[c] : 0.0f;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r)
+            if (c_ok && row0 + r < n)
+                ((float *)out)[(row0 + r) * out_stride + c] = a * (float)(K - 2 * acc[r]);
+    }
+}
+
+} // namespace
+
+int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,
+                   int32_t kwords, const uint64_t *wbits, int32_t M, int64_t w_stride,
+                   int epilogue, const int32_t *T, const float *alpha, const void *out,
+                   int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, n >= 0 && K >= 1 && kwords >= 1 && M >= 1, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: n=%lld K=%d kwords=%d M=%d", (long long)n, K, kwords, M);
+    BG_REQUIRE(ctx, (int64_t)K <= (int64_t)kwords * 64, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: K=%d logical bits do not fit kwords=%d words", K, kwords);
+    BG_REQUIRE(ctx, x_stride >= kwords && w_stride >= kwords, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: x_stride=%lld w_stride=%lld < kwords=%d", (long long)x_stride,
+               (long long)w_stride, kwords);
+    BG_REQUIRE(ctx,
+               epilogue == BITGNN_EPI_RAW_I32 || epilogue == BITGNN_EPI_THRESH_BITS ||
+                   epilogue == BITGNN_EPI_SCALE_F32,
+               BITGNN_ERR_INVALID_ARG, "bitgnn_bgemm: epilogue=%d", epilogue);
+    const int64_t need = epilogue == BITGNN_EPI_THRESH_BITS ? (M + 63) / 64 : M;
+    BG_REQUIRE(ctx, out_stride >= need, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: out_stride=%lld < %lld", (long long)out_stride, (long long)need);
+    BG_REQUIRE(ctx, wbits && (n == 0 || (xbits && out)), BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: null pointer");
+    BG_REQUIRE(ctx, epilogue != BITGNN_EPI_THRESH_BITS || T, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: THRESH_BITS needs T");
+    BG_REQUIRE(ctx, epilogue != BITGNN_EPI_SCALE_F32 || alpha, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm: SCALE_F32 needs alpha");
+    BG_REQUIRE(ctx,
+               bg_aligned(xbits, 8) && bg_aligned(wbits, 8) && bg_aligned(T, 4) &&
+                   bg_aligned(alpha, 4) &&
+                   bg_aligned(out, epilogue == BITGNN_EPI_THRESH_BITS ? 8 : 4),
+               BITGNN_ERR_ALIGNMENT, "bitgnn_bgemm: misaligned pointer");
+    return BITGNN_OK;
+}
+
+int bg_launch_bgemm(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
+                    int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits, int32_t M,
+                    int64_t w_stride, int epilogue, const int32_t *T, const float *alpha,
+                    void *out, int64_t out_stride)
+{
+    if (n == 0)
+        return BITGNN_OK;
+    const int64_t gx = (n + kWaves * kRows - 1) / (kWaves * kRows);
+    BG_REQUIRE(ctx, gx < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bgemm: n too large");
+    dim3 grid((unsigned)gx, (unsigned)((M + 63) / 64));
+    dim3 block(kWaves * 64);
+    const uint32_t *x32 = (const uint32_t *)xbits;
+    const uint32_t *w32 = (const uint32_t *)wbits;
+    const int32_t kw32 = kwords * 2;
+    switch (epilogue) {
+    case BITGNN_EPI_THRESH_BITS:
+        bgemm_kernel<BITGNN_EPI_THRESH_BITS><<<grid, block, 0, s>>>(
+            x32, n, x_stride * 2, K, kw32, w32, M, w_stride * 2, T, alpha, out, out_stride);
+        break;
+    case BITGNN_EPI_RAW_I32:
+        bgemm_kernel<BITGNN_EPI_RAW_I32><<<grid, block, 0, s>>>(
+            x32, n, x_stride * 2, K, kw32, w32, M, w_stride * 2, T, alpha, out, out_stride);
+        break;
+    default:
+        bgemm_kernel<BITGNN_EPI_SCALE_F32><<<grid, block, 0, s>>>(
+            x32, n, x_stride * 2, K, kw32, w32, M, w_stride * 2, T, alpha, out, out_stride);
+        break;
+    }
+    BG_LAUNCH_CHECK(ctx, "bitgnn_bgemm");
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_bgemm(bitgnn_ctx *ctx, void *stream, const uint64_t *xbits, int64_t n,
+                            int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits,
+                            int32_t M, int64_t w_stride, int epilogue, const int32_t *T,
+                            const float *alpha, void *out, int64_t out_stride)
+{
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride, epilogue, T,
+                            alpha, out, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    return bg_launch_bgemm(ctx, (hipStream_t)stream, xbits, n, x_stride, K, kwords, wbits, M,
+                           w_stride, epilogue, T, alpha, out, out_stride);
+}

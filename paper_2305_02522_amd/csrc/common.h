@@ -1,0 +1,100 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/bitgnn.h"
+
+#define BITGNN_WAVE 64
+
+struct bitgnn_ctx {
+    int device;           // -1: validation-only context
+    char err[256];
+    uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
+    size_t seed_table_words;
+};
+
+struct bitgnn_adj {
+    int device;
+    int64_t n;
+    int64_t nnz;
+    int64_t max_degree;
+    uint32_t *rowptr; // [n+1]
+    int32_t *col;     // [nnz]
+    int32_t *deg;     // [n]
+    int32_t *order;   // [n] rows by decreasing degree
+    size_t device_bytes;
+};
+
+static inline int bitgnn_fail(bitgnn_ctx *ctx, int code, const char *fmt, ...)
+    __attribute__((format(printf, 3, 4)));
+static inline int bitgnn_fail(bitgnn_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define BG_REQUIRE(ctx, cond, code, ...)                                                          \
+    do {                                                                                          \
+        if (!(cond))                                                                              \
+            return bitgnn_fail((ctx), (code), __VA_ARGS__);                                       \
+    } while (0)
+
+#define BG_HIP(ctx, call)                                                                         \
+    do {                                                                                          \
+        hipError_t e_ = (call);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return bitgnn_fail((ctx), BITGNN_ERR_HIP, "%s failed: %s (%d)", #call,                \
+                               hipGetErrorString(e_), (int)e_);                                   \
+    } while (0)
+
+// After a kernel launch: report launch-time errors (bad configuration etc.).
+#define BG_LAUNCH_CHECK(ctx, name)                                                                \
+    do {                                                                                          \
+        hipError_t e_ = hipGetLastError();                                                        \
+        if (e_ != hipSuccess)                                                                     \
+            return bitgnn_fail((ctx), BITGNN_ERR_HIP, "launch of %s failed: %s (%d)", name,       \
+                               hipGetErrorString(e_), (int)e_);                                   \
+    } while (0)
+
+static inline bool bg_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Calls with a validation-only context stop here, after all argument checks.
+#define BG_NEED_DEVICE(ctx)                                                                       \
+    do {                                                                                          \
+        if ((ctx)->device < 0)                                                                    \
+            return bitgnn_fail((ctx), BITGNN_ERR_NO_DEVICE,                                       \
+                               "arguments valid; context has no GPU");                            \
+    } while (0)
+
+// Internal launchers shared across translation units (arguments already validated).
+int bg_launch_bgemm(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
+                    int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits, int32_t M,
+                    int64_t w_stride, int epilogue, const int32_t *T, const float *alpha,
+                    void *out, int64_t out_stride);
+int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint64_t *hbits,
+                    int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
+                    int64_t out_stride);
+int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const int32_t *Z,
+                       int32_t M, int64_t z_stride, const float *alpha, void *out,
+                       int64_t out_stride);
+
+// Argument validation of the public calls, shared with the layer drivers.
+int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,
+                   int32_t kwords, const uint64_t *wbits, int32_t M, int64_t w_stride,
+                   int epilogue, const int32_t *T, const float *alpha, const void *out,
+                   int64_t out_stride);
+int bg_check_bspmm(bitgnn_ctx *ctx, const bitgnn_adj *adj, const uint64_t *hbits, int32_t C,
+                   int64_t h_stride, int epilogue, const int32_t *T, const void *out,
+                   int64_t out_stride);
+int bg_check_spmm_i32(bitgnn_ctx *ctx, const bitgnn_adj *adj, const int32_t *Z, int32_t M,
+                      int64_t z_stride, int64_t z_abs_bound, const void *out, int64_t out_stride);

@@ -1,0 +1,125 @@
+// Layer drivers: the high-level functions of Section 3.1.2 (a BMM followed by a
+// BSpMM for GCN; an aggregation, a concatenation and a BMM for GraphSAGE /
+// GraphConv), in the "binary aggregation" recipe of Table 3's caption.  They
+// only validate and enqueue the kernels of the other files on one stream.
+#include "common.h"
+
+extern "C" int bitgnn_gcn_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
+                                const uint64_t *wbits, int32_t M, int64_t w_stride,
+                                const int32_t *T_mm, const int32_t *T_agg, uint64_t *tmp_bits,
+                                uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_layer: adj is null");
+    const int64_t n = adj->n;
+    const int64_t mw = ((int64_t)M + 63) / 64;
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                            BITGNN_EPI_THRESH_BITS, T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_bspmm(ctx, adj, tmp_bits, M, mw, BITGNN_EPI_THRESH_BITS, T_agg, out_bits,
+                        out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                         BITGNN_EPI_THRESH_BITS, T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_bspmm(ctx, s, adj, tmp_bits, M, mw, BITGNN_EPI_THRESH_BITS, T_agg, out_bits,
+                           out_stride);
+}
+
+extern "C" int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                    const uint64_t *xbits, int64_t x_stride, int32_t K,
+                                    int32_t kwords, const uint64_t *wbits, int32_t M,
+                                    int64_t w_stride, const float *alpha, int32_t *tmp_i32,
+                                    float *logits, int64_t ldo)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_out_layer: adj is null");
+    BG_REQUIRE(ctx, alpha, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_out_layer: alpha is null");
+    const int64_t n = adj->n;
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                            BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_i32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_spmm_i32(ctx, adj, tmp_i32, M, M, K, logits, ldo);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_REQUIRE(ctx, bg_aligned(alpha, 4), BITGNN_ERR_ALIGNMENT,
+               "bitgnn_gcn_out_layer: misaligned alpha");
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                         BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_i32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_spmm_i32(ctx, s, adj, tmp_i32, M, M, alpha, logits, ldo);
+}
+
+extern "C" int bitgnn_sage_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                 uint64_t *cat_bits, int32_t K_in, const uint64_t *wbits,
+                                 int32_t M, int64_t w_stride, const int32_t *T_agg,
+                                 const int32_t *T_mm, uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_layer: adj is null");
+    BG_REQUIRE(ctx, K_in >= 1 && K_in <= (1 << 29), BITGNN_ERR_INVALID_ARG,
+               "bitgnn_sage_layer: K_in=%d", K_in);
+    BG_REQUIRE(ctx, cat_bits, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_layer: cat_bits is null");
+    const int64_t n = adj->n;
+    const int32_t kw = (K_in + 63) / 64;
+    int rc = bg_check_bspmm(ctx, adj, cat_bits, K_in, 2 * kw, BITGNN_EPI_THRESH_BITS, T_agg,
+                            cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_bgemm(ctx, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                        BITGNN_EPI_THRESH_BITS, T_mm, nullptr, out_bits, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bspmm(ctx, s, adj, cat_bits, K_in, 2 * kw, BITGNN_EPI_THRESH_BITS, T_agg,
+                         cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                           BITGNN_EPI_THRESH_BITS, T_mm, nullptr, out_bits, out_stride);
+}
+
+extern "C" int bitgnn_sage_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                     uint64_t *cat_bits, int32_t K_in, const uint64_t *wbits,
+                                     int32_t M, int64_t w_stride, const int32_t *T_agg,
+                                     const float *alpha, float *logits, int64_t ldo)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_out_layer: adj is null");
+    BG_REQUIRE(ctx, K_in >= 1 && K_in <= (1 << 29), BITGNN_ERR_INVALID_ARG,
+               "bitgnn_sage_out_layer: K_in=%d", K_in);
+    BG_REQUIRE(ctx, cat_bits, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_out_layer: cat_bits is null");
+    const int64_t n = adj->n;
+    const int32_t kw = (K_in + 63) / 64;
+    int rc = bg_check_bspmm(ctx, adj, cat_bits, K_in, 2 * kw, BITGNN_EPI_THRESH_BITS, T_agg,
+                            cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_bgemm(ctx, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                        BITGNN_EPI_SCALE_F32, nullptr, alpha, logits, ldo);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bspmm(ctx, s, adj, cat_bits, K_in, 2 * kw, BITGNN_EPI_THRESH_BITS, T_agg,
+                         cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                           BITGNN_EPI_SCALE_F32, nullptr, alpha, logits, ldo);
+}

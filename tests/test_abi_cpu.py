@@ -1,0 +1,96 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the
+header declares, and its argument validation (forced from the host through a
+GPU-less context) returns the documented codes."""
+import os
+import re
+
+import pytest
+
+from paper_2305_02522_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bitgnn.h")).read()
+    declared = set(re.findall(r"\b(bitgnn_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 17
+    assert declared == set(B.EXPORTS)
+    import ctypes
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.fixture()
+def vctx():
+    ctx = B.Context(-1)
+    yield ctx
+    ctx.close()
+
+
+def _code(fn, *a):
+    with pytest.raises(B.BitgnnError) as e:
+        fn(*a)
+    return e.value.code
+
+
+P8 = 0x1000       # fake, aligned, never dereferenced: validation contexts do not launch
+
+
+def test_pack_validation(vctx):
+    assert _code(B.pack_f32, vctx, P8, 4, 100, 100, None, P8, 2) == B.ERR_NO_DEVICE
+    assert "no GPU" in vctx.last_error()
+    assert _code(B.pack_f32, vctx, P8, 4, 100, 99, None, P8, 2) == B.ERR_INVALID_ARG   # ldx < K
+    assert _code(B.pack_f32, vctx, P8, 4, 100, 100, None, P8, 1) == B.ERR_INVALID_ARG  # stride
+    assert _code(B.pack_f32, vctx, None, 4, 100, 100, None, P8, 2) == B.ERR_INVALID_ARG
+    assert _code(B.pack_f32, vctx, P8, 4, 0, 100, None, P8, 2) == B.ERR_INVALID_ARG
+    assert _code(B.pack_f32, vctx, P8 + 2, 4, 100, 100, None, P8, 2) == B.ERR_ALIGNMENT
+    assert _code(B.pack_f32, vctx, P8, 4, 100, 100, None, P8 + 4, 2) == B.ERR_ALIGNMENT
+    assert _code(B.pack_i8, vctx, P8 + 1, 4, 100, 100, P8, 2) == B.ERR_NO_DEVICE      # bytes: any
+    B.pack_f32(vctx, None, 0, 100, 100, None, None, 2)                                 # n = 0: no-op
+    assert _code(B.pack_weights_i8, vctx, P8, 10, 4, 3, P8, 1) == B.ERR_INVALID_ARG    # ldw < M
+
+
+def test_adj_build_validation(vctx):
+    assert _code(B.adj_build, vctx, P8, P8, 10, 5, 3) == B.ERR_NO_DEVICE
+    assert _code(B.adj_build, vctx, P8, P8, 10, 0, 0) == B.ERR_INVALID_ARG
+    assert _code(B.adj_build, vctx, P8, P8, -1, 5, 0) == B.ERR_INVALID_ARG
+    assert _code(B.adj_build, vctx, P8, P8, 10, 5, 4) == B.ERR_INVALID_ARG             # flags
+    assert _code(B.adj_build, vctx, None, P8, 10, 5, 0) == B.ERR_INVALID_ARG
+    assert _code(B.adj_build, vctx, P8 + 2, P8, 10, 5, 0) == B.ERR_ALIGNMENT
+    assert _code(B.adj_build, vctx, P8, P8, 1 << 30, 5, 1) == B.ERR_RANGE              # 2E+N >= 2^31
+
+
+def test_bgemm_validation(vctx):
+    ok = (P8, 10, 2, 100, 2, P8, 7, 2)
+    assert _code(B.bgemm, vctx, *ok, B.EPI_THRESH_BITS, P8, None, P8, 1) == B.ERR_NO_DEVICE
+    assert _code(B.bgemm, vctx, *ok, B.EPI_THRESH_BITS, None, None, P8, 1) == B.ERR_INVALID_ARG
+    assert _code(B.bgemm, vctx, *ok, B.EPI_SCALE_F32, None, None, P8, 7) == B.ERR_INVALID_ARG
+    assert _code(B.bgemm, vctx, *ok, B.EPI_RAW_I32, None, None, P8, 6) == B.ERR_INVALID_ARG
+    assert _code(B.bgemm, vctx, *ok, 3, None, None, P8, 7) == B.ERR_INVALID_ARG
+    assert _code(B.bgemm, vctx, P8, 10, 1, 100, 2, P8, 7, 2, 0, None, None, P8, 7) == \
+        B.ERR_INVALID_ARG                                                              # x_stride
+    assert _code(B.bgemm, vctx, P8, 10, 2, 129, 2, P8, 7, 2, 0, None, None, P8, 7) == \
+        B.ERR_INVALID_ARG                                                              # K > bits
+    assert _code(B.bgemm, vctx, P8 + 4, 10, 2, 100, 2, P8, 7, 2, 0, None, None, P8, 7) == \
+        B.ERR_ALIGNMENT
+    assert _code(B.bgemm, vctx, *ok, B.EPI_THRESH_BITS, P8, None, P8 + 4, 1) == B.ERR_ALIGNMENT
+    assert _code(B.bgemm, vctx, *ok, B.EPI_RAW_I32, None, None, P8 + 4, 7) == B.ERR_NO_DEVICE
+
+
+def test_aggregation_and_layer_validation(vctx):
+    assert _code(B.bspmm, vctx, None, P8, 64, 1, B.EPI_THRESH_BITS, P8, P8, 1) == B.ERR_INVALID_ARG
+    assert _code(B.spmm_i32, vctx, None, P8, 7, 7, 64, None, P8, 7) == B.ERR_INVALID_ARG
+    assert _code(B.gcn_layer, vctx, None, P8, 2, 100, 2, P8, 64, 2, P8, P8, P8, P8, 1) == \
+        B.ERR_INVALID_ARG
+    assert _code(B.gcn_out_layer, vctx, None, P8, 2, 100, 2, P8, 7, 2, P8, P8, P8, 7) == \
+        B.ERR_INVALID_ARG
+    assert _code(B.sage_layer, vctx, None, P8, 100, P8, 64, 4, P8, P8, P8, 2) == B.ERR_INVALID_ARG
+    assert _code(B.sage_out_layer, vctx, None, P8, 100, P8, 7, 4, P8, P8, P8, 7) == \
+        B.ERR_INVALID_ARG
+
+
+def test_ctx_create_rejects_bad_device():
+    with pytest.raises(B.BitgnnError):
+        B.Context(-2)

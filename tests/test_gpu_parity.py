@@ -1,0 +1,319 @@
+"""GPU parity: every kernel of the library against the CPU oracle, element by
+element, on the same seeded inputs.  Integers, packed words and indices must be
+bit-exact; float logits within 1e-5 relative (one float multiply per logit)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2305_02522_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SYM_LOOPS = W.ADJ_SYMMETRIZE | W.ADJ_ADD_SELF_LOOPS
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2305_02522_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+
+
+def words_np(t):
+    """int64 torch tensor of packed words -> uint64 numpy."""
+    return t.cpu().numpy().view(np.uint64)
+
+
+def rel_close(got, ref, tol=1e-5):
+    denom = np.maximum(np.abs(ref), 1e-30)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64)) / denom
+    err[got == ref] = 0
+    return err.max() <= tol
+
+
+# ------------------------------------------------------------------ a1: pack
+@pytest.mark.parametrize("n,K,pad_ld,pad_out", [
+    (1, 1, 0, 0), (3, 63, 0, 0), (5, 64, 3, 1), (130, 65, 0, 0), (257, 100, 4, 2),
+    (1000, 602, 0, 0), (2708, 1433, 0, 0), (64, 4096, 0, 0), (70001, 128, 0, 0)])
+def test_pack_f32(B, ctx, n, K, pad_ld, pad_out):
+    r = np.random.default_rng(n * 7919 + K)
+    ldx = K + pad_ld
+    x = r.standard_normal((n, ldx)).astype(np.float32)
+    x[r.random((n, ldx)) < 0.05] = 0.0           # exact ties
+    x[r.random((n, ldx)) < 0.02] = -0.0
+    kw = (K + 63) // 64
+    stride = kw + pad_out
+    out = torch.full((n, stride), -1, dtype=torch.int64, device="cuda")
+    B.pack_f32(ctx, dev(x), n, K, ldx, None, out, stride)
+    torch.cuda.synchronize()
+    ref = orc.to_words(orc.bin_f32(x[:, :K]))
+    got = words_np(out)
+    assert np.array_equal(got[:, :kw], ref)
+    assert np.all(got[:, kw:] == np.uint64(0xFFFFFFFFFFFFFFFF))      # untouched
+    # per-column threshold (folded BatchNorm)
+    tau = r.standard_normal(K).astype(np.float32)
+    x[:, :K][r.random((n, K)) < 0.05] = 0
+    x[0, :K] = tau                                                     # ties -> +1
+    B.pack_f32(ctx, dev(x), n, K, ldx, dev(tau), out, stride)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(out)[:, :kw], orc.to_words(orc.bin_f32(x[:, :K], tau)))
+
+
+@pytest.mark.parametrize("n,K", [(1, 1), (77, 100), (300, 1433), (5000, 64)])
+def test_pack_i8_and_weights(B, ctx, n, K):
+    r = np.random.default_rng(K)
+    x = r.integers(-128, 128, size=(n, K), dtype=np.int8)
+    kw = (K + 63) // 64
+    out = torch.zeros((n, kw), dtype=torch.int64, device="cuda")
+    B.pack_i8(ctx, dev(x), n, K, K, out, kw)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(out), orc.to_words(orc.bin_i8(x)))
+    # weights: transposed packing, w is [K][M]
+    M = 37
+    w = W.pm1(r, (K, M))
+    wb = torch.zeros((M, kw + 1), dtype=torch.int64, device="cuda")
+    B.pack_weights_i8(ctx, dev(w), K, M, M, wb, kw + 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(wb)[:, :kw], orc.to_words(np.ascontiguousarray(w.T)))
+
+
+# ------------------------------------------------------------------ a2: adjacency
+def _csr_from_gpu(B, adj):
+    import ctypes
+    rp_p, col_p, deg_p = adj.csr_pointers()
+    n, nnz = adj.n, adj.nnz
+    rp = torch.empty(n + 1, dtype=torch.int32, device="cuda")
+    col = torch.empty(max(nnz, 1), dtype=torch.int32, device="cuda")
+    deg = torch.empty(n, dtype=torch.int32, device="cuda")
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    assert hip.hipMemcpy(rp.data_ptr(), rp_p, 4 * (n + 1), 3) == 0
+    if nnz:
+        assert hip.hipMemcpy(col.data_ptr(), col_p, 4 * nnz, 3) == 0
+    assert hip.hipMemcpy(deg.data_ptr(), deg_p, 4 * n, 3) == 0
+    torch.cuda.synchronize()
+    return (rp.cpu().numpy().view(np.uint32).astype(np.int64), col.cpu().numpy()[:nnz],
+            deg.cpu().numpy())
+
+
+@pytest.mark.parametrize("n,e,flags,seed", [
+    (1, 0, 0, 0), (1, 0, W.ADJ_ADD_SELF_LOOPS, 0), (5, 0, 0, 1), (7, 30, 0, 2),
+    (100, 1000, W.ADJ_SYMMETRIZE, 3), (1000, 5000, SYM_LOOPS, 4),
+    (4097, 70000, SYM_LOOPS, 5), (300000, 900000, SYM_LOOPS, 6), (50, 20000, SYM_LOOPS, 7)])
+def test_adj_build_matches_set_definition(B, ctx, n, e, flags, seed):
+    r = np.random.default_rng(seed)
+    src, dst = W.random_graph(r, n, e)
+    s = dev(src) if e else None
+    d = dev(dst) if e else None
+    adj = B.adj_build(ctx, s, d, e, n, flags)
+    rp_ref, col_ref = orc.adjacency(src, dst, n, flags)
+    rp, col, deg = _csr_from_gpu(B, adj)
+    assert adj.nnz == rp_ref[-1]
+    assert np.array_equal(rp, rp_ref)
+    assert np.array_equal(col, col_ref)
+    assert np.array_equal(deg, orc.degrees(rp_ref))
+    assert adj.max_degree == (orc.degrees(rp_ref).max() if n else 0)
+    adj.close()
+
+
+def test_adj_build_rejects_out_of_range(B, ctx):
+    src = dev(np.array([0, 1, 5], dtype=np.int32))
+    dst = dev(np.array([1, 2, 0], dtype=np.int32))
+    with pytest.raises(B.BitgnnError) as e:
+        B.adj_build(ctx, src, dst, 3, 5, 0)
+    assert e.value.code == B.ERR_INDEX_RANGE
+    src = dev(np.array([0, -1], dtype=np.int32))
+    dst = dev(np.array([1, 2], dtype=np.int32))
+    with pytest.raises(B.BitgnnError) as e:
+        B.adj_build(ctx, src, dst, 2, 5, 0)
+    assert e.value.code == B.ERR_INDEX_RANGE
+
+
+# ------------------------------------------------------------------ a3: BGEMM
+def _pack_host(v):
+    return dev(orc.to_words(v).view(np.int64))
+
+
+@pytest.mark.parametrize("n,K,M", [
+    (1, 1, 1), (5, 63, 7), (129, 64, 64), (300, 65, 65), (1000, 100, 41), (777, 602, 128),
+    (500, 1433, 64), (2048, 512, 256), (100, 1000, 47), (4099, 128, 40), (33, 2100, 130)])
+def test_bgemm_three_epilogues(B, ctx, n, K, M):
+    r = np.random.default_rng(K * 1000 + M)
+    x = W.pm1(r, (n, K))
+    w = W.pm1(r, (K, M))
+    z = orc.bmm(x, w)
+    kw = (K + 63) // 64
+    xb = _pack_host(x)
+    wb = _pack_host(np.ascontiguousarray(w.T))
+    # RAW
+    out = torch.full((n, M + 3), 12345, dtype=torch.int32, device="cuda")
+    B.bgemm(ctx, xb, n, kw, K, kw, wb, M, kw, B.EPI_RAW_I32, None, None, out, M + 3)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:, :M], z)
+    assert np.all(got[:, M:] == 12345)
+    # THRESH
+    t = r.integers(-6, 7, size=M).astype(np.int32)
+    mw = (M + 63) // 64
+    ob = torch.full((n, mw), -1, dtype=torch.int64, device="cuda")
+    B.bgemm(ctx, xb, n, kw, K, kw, wb, M, kw, B.EPI_THRESH_BITS, dev(t), None, ob, mw)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(ob), orc.to_words(orc.rebin(z, t)))       # pad bits 0
+    # SCALE
+    alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
+    of = torch.zeros((n, M), dtype=torch.float32, device="cuda")
+    B.bgemm(ctx, xb, n, kw, K, kw, wb, M, kw, B.EPI_SCALE_F32, None, dev(alpha), of, M)
+    torch.cuda.synchronize()
+    assert rel_close(of.cpu().numpy(), orc.scale(z, alpha))
+
+
+def test_bgemm_segmented_k_with_interior_pad_bits(B, ctx):
+    # [self | nbr] rows: two 100-bit segments, each padded to 128 bits, K = 200
+    r = np.random.default_rng(99)
+    n, k_in, M = 300, 100, 70
+    a, b = W.pm1(r, (n, k_in)), W.pm1(r, (n, k_in))
+    w = W.pm1(r, (2 * k_in, M))
+    z = orc.bmm(orc.concat(a, b), w)
+    xb = dev(np.concatenate([orc.to_words(a), orc.to_words(b)], axis=1).view(np.int64))
+    wt = np.ascontiguousarray(w.T)
+    wb = dev(np.concatenate([orc.to_words(wt[:, :k_in]), orc.to_words(wt[:, k_in:])],
+                            axis=1).view(np.int64))
+    out = torch.zeros((n, M), dtype=torch.int32, device="cuda")
+    B.bgemm(ctx, xb, n, 4, 2 * k_in, 4, wb, M, 4, B.EPI_RAW_I32, None, None, out, M)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), z)
+
+
+# ------------------------------------------------------------------ a4: bit-SpMM
+def _graph(B, ctx, n, e, flags, seed, hubs=0):
+    r = np.random.default_rng(seed)
+    src, dst = W.random_graph(r, n, e)
+    if hubs:                     # a few very long rows
+        hs = r.integers(0, n, size=hubs * n // 2, dtype=np.int32) % max(hubs, 1)
+        hd = r.integers(0, n, size=hubs * n // 2, dtype=np.int32)
+        src, dst = np.concatenate([src, hs]), np.concatenate([dst, hd])
+    adj = B.adj_build(ctx, dev(src), dev(dst), len(src), n, flags)
+    rp, col = orc.adjacency(src, dst, n, flags)
+    return adj, rp, col, r
+
+
+@pytest.mark.parametrize("n,e,C,flags,hubs", [
+    (1, 0, 1, W.ADJ_ADD_SELF_LOOPS, 0), (9, 20, 7, SYM_LOOPS, 0), (100, 700, 32, SYM_LOOPS, 0),
+    (257, 3000, 33, W.ADJ_SYMMETRIZE, 0), (1000, 20000, 64, SYM_LOOPS, 0),
+    (3000, 40000, 100, W.ADJ_SYMMETRIZE, 0), (5000, 100000, 128, SYM_LOOPS, 2),
+    (2000, 30000, 256, SYM_LOOPS, 0), (1500, 9000, 500, W.ADJ_SYMMETRIZE, 0),
+    (40000, 100000, 128, SYM_LOOPS, 1), (700, 300, 65, 0, 0)])
+def test_bspmm_raw_and_threshold(B, ctx, n, e, C, flags, hubs):
+    adj, rp, col, r = _graph(B, ctx, n, e, flags, n + C, hubs)
+    v = W.pm1(r, (n, C))
+    s = orc.spmm_pm1(rp, col, v)
+    cw = (C + 63) // 64
+    hb = _pack_host(v)
+    raw = torch.full((n, C + 1), 777, dtype=torch.int32, device="cuda")
+    B.bspmm(ctx, adj, hb, C, cw, B.EPI_RAW_I32, None, raw, C + 1)
+    torch.cuda.synchronize()
+    got = raw.cpu().numpy()
+    assert np.array_equal(got[:, :C], s)
+    assert np.all(got[:, C] == 777)
+    for t in (np.zeros(C, dtype=np.int32),                       # the paper's c >= 0
+              r.integers(-4, 5, size=C).astype(np.int32),
+              r.integers(-40000, 40000, size=C).astype(np.int32),
+              np.full(C, 2**31 - 1, dtype=np.int32), np.full(C, -2**31, dtype=np.int32)):
+        ob = torch.full((n, cw + 1), -1, dtype=torch.int64, device="cuda")
+        B.bspmm(ctx, adj, hb, C, cw, B.EPI_THRESH_BITS, dev(t), ob, cw + 1)
+        torch.cuda.synchronize()
+        gw = words_np(ob)
+        assert np.array_equal(gw[:, :cw], orc.to_words(orc.rebin(s, t)))
+        assert np.all(gw[:, cw] == np.uint64(0xFFFFFFFFFFFFFFFF))
+    adj.close()
+
+
+def test_bspmm_star_graph_long_row(B, ctx):
+    # one row with 70,000 neighbours: needs the 20-plane counters
+    n, C = 70001, 96
+    src = np.zeros(n - 1, dtype=np.int32)
+    dst = np.arange(1, n, dtype=np.int32)
+    adj = B.adj_build(ctx, dev(src), dev(dst), n - 1, n, SYM_LOOPS)
+    rp, col = orc.adjacency(src, dst, n, SYM_LOOPS)
+    assert adj.max_degree == n
+    r = np.random.default_rng(5)
+    v = (r.random((n, C)) < 0.5003).astype(np.int8) * 2 - 1
+    s = orc.spmm_pm1(rp, col, v)
+    t = r.integers(-300, 300, size=C).astype(np.int32)
+    ob = torch.zeros((n, 2), dtype=torch.int64, device="cuda")
+    B.bspmm(ctx, adj, _pack_host(v), C, 2, B.EPI_THRESH_BITS, dev(t), ob, 2)
+    raw = torch.zeros((n, C), dtype=torch.int32, device="cuda")
+    B.bspmm(ctx, adj, _pack_host(v), C, 2, B.EPI_RAW_I32, None, raw, C)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw.cpu().numpy(), s)
+    assert np.array_equal(words_np(ob), orc.to_words(orc.rebin(s, t)))
+    adj.close()
+
+
+# ------------------------------------------------------------------ a5: integer aggregation
+@pytest.mark.parametrize("n,e,M", [(50, 200, 1), (1000, 9000, 7), (3000, 50000, 41),
+                                   (500, 4000, 64), (300, 2000, 130)])
+def test_spmm_i32(B, ctx, n, e, M):
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + M)
+    z = r.integers(-600, 601, size=(n, M)).astype(np.int32)
+    y = orc.spmm_i64(rp, col, z)
+    out = torch.zeros((n, M), dtype=torch.int32, device="cuda")
+    B.spmm_i32(ctx, adj, dev(z), M, M, 600, None, out, M)
+    alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
+    of = torch.zeros((n, M), dtype=torch.float32, device="cuda")
+    B.spmm_i32(ctx, adj, dev(z), M, M, 600, dev(alpha), of, M)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), y)
+    assert rel_close(of.cpu().numpy(), orc.scale(y, alpha))
+    with pytest.raises(B.BitgnnError) as ex:
+        B.spmm_i32(ctx, adj, dev(z), M, M, 2**31 - 1, None, out, M)
+    assert ex.value.code == B.ERR_RANGE
+    adj.close()
+
+
+# ------------------------------------------------------------------ whole models
+def _run_model(B, ctx, wl):
+    adj = B.adj_build(ctx, dev(wl.src), dev(wl.dst), len(wl.src), wl.n, wl.adj_flags)
+    model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
+    x = dev(wl.x).to(torch.float32)
+    logits = model.forward(x)
+    torch.cuda.synchronize()
+    return adj, model, logits.cpu().numpy()
+
+
+def _check_model(B, ctx, wl):
+    adj, model, logits = _run_model(B, ctx, wl)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    assert adj.nnz == rp[-1]
+    ref, hidden = orc.forward(wl.model, rp, col, orc.bin_f32(wl.x.astype(np.float32)),
+                              wl.layers, return_hidden=True)
+    # hidden activations: packed words bit-exact (buffer of layer l+1 = output of layer l)
+    for l, h in enumerate(hidden):
+        kw = (h.shape[1] + 63) // 64
+        got = words_np(model.act[l + 1])[:, :kw]
+        assert np.array_equal(got, orc.to_words(h)), f"hidden layer {l}"
+    assert rel_close(logits, ref), "logits"
+    adj.close()
+
+
+@pytest.mark.parametrize("cfg,kw", [
+    (1, {}), (1, {"zero_thresholds": True}), (2, {"n": 1 << 13}), (3, {"n": 20000}),
+    (4, {"n": 6000, "mean_deg": 120.0}), (5, {"n": 50000, "mean_deg": 20.0})])
+def test_model_small(B, ctx, cfg, kw):
+    _check_model(B, ctx, W.make_workload(cfg, **kw))
+
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_model_full_size(B, ctx, cfg):
+    _check_model(B, ctx, W.make_workload(cfg))
