@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the binary-GNN hot path on one MI355X.
+
+A step is one full-graph inference of the configured model: bit-pack of the
+float features, then every layer (XNOR-popcount BGEMM, bit-SpMM with fused
+threshold/re-pack, integer aggregation + scale for the logits), with all inputs
+and the prebuilt adjacency already resident in HBM.  The adjacency build and the
+weight packing are done once before the timed region (they are offline steps in
+the paper) and their time is reported separately.
+
+Prints ONE JSON line (see the design doc for the definition of every field).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
+VALU_PEAK_TLOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, 32-bit lane-ops
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def op_models(wl, nnz):
+    """Per-op work (bit-ops) and algorithmic bytes / lane-ops, keyed like forward_ops labels."""
+    n = wl.n
+    w64 = lambda k: (k + 63) // 64
+    idx_bytes = 4 * nnz + 4 * (n + 1)       # the stored format is CSR: 4 B per non-zero
+    ops = {}
+    k0 = wl.dims[0]
+    ops["pack_f32"] = dict(work=0, bytes=4 * n * k0 + 8 * n * w64(k0), bound="hbm")
+    nl = len(wl.layers)
+    for l in range(nl):
+        k_in, m = wl.dims[l], wl.dims[l + 1]
+        last = l == nl - 1
+        if wl.model == "gcn":
+            kw = w64(k_in)
+            out_b = 4 * n * m if last else 8 * n * w64(m)
+            ops[f"L{l}.bgemm"] = dict(work=n * k_in * m, bytes=8 * kw * (n + m) + out_b,
+                                      lane_ops=2 * n * m * ((k_in + 31) // 32), bound="alu")
+            if last:
+                ops[f"L{l}.spmm_i32"] = dict(work=nnz * m, bytes=idx_bytes + 8 * n * m,
+                                             bound="hbm")
+            else:
+                ops[f"L{l}.bspmm"] = dict(work=nnz * m,
+                                          bytes=idx_bytes + 16 * n * w64(m) + 4 * n + 4 * m,
+                                          bound="hbm")
+        else:
+            kw = w64(k_in)
+            ops[f"L{l}.bspmm"] = dict(work=nnz * k_in,
+                                      bytes=idx_bytes + 16 * n * kw + 4 * n + 4 * k_in,
+                                      bound="hbm")
+            out_b = 4 * n * m if last else 8 * n * w64(m)
+            ops[f"L{l}.bgemm"] = dict(work=n * 2 * k_in * m, bytes=16 * kw * (n + m) + out_b,
+                                      lane_ops=2 * n * m * 4 * kw, bound="alu")
+    return ops
+
+
+def cpu_baseline(wl, rows):
+    """The oracle, as it stands, on the first `rows` nodes of every step of the model
+    (inputs of the right shape and distribution; hidden activations are seeded +-1
+    draws, not GPU results).  Returns (bit-ops per second, seconds, threads)."""
+    import numpy as np
+    from oracle import oracle as orc
+    from paper_2305_02522_amd import workloads as W
+    rng = np.random.default_rng(7)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    rows = min(rows, wl.n)
+    deg_rows = int(rp[rows] - rp[0])
+    work, secs = 0, 0.0
+    x = wl.x[:rows].astype(np.float32)
+    t = time.perf_counter()
+    v = orc.bin_f32(x)
+    secs += time.perf_counter() - t
+    nl = len(wl.layers)
+    for l, p in enumerate(wl.layers):
+        k_in, m = wl.dims[l], wl.dims[l + 1]
+        last = l == nl - 1
+        # untimed: seeded stand-ins for the activations of ALL nodes that the
+        # aggregation of the sampled rows gathers from
+        if wl.model == "gcn" and last:
+            gathered = rng.integers(-k_in, k_in + 1, size=(wl.n, m)).astype(np.int64)
+        else:
+            gathered = W.pm1(rng, (wl.n, m if wl.model == "gcn" else k_in))
+        t = time.perf_counter()
+        if wl.model == "gcn":
+            z = orc.bmm(v, p.w)
+            if last:
+                orc.scale(orc.spmm_i64(rp, col, gathered, (0, rows)), p.alpha)
+            else:
+                orc.rebin(z, p.t_mm)
+                v = orc.rebin(orc.spmm_pm1(rp, col, gathered, (0, rows)), p.t_agg)
+            work += rows * k_in * m + deg_rows * m
+        else:
+            nb = orc.rebin(orc.spmm_pm1(rp, col, gathered, (0, rows)), p.t_agg)
+            z = orc.bmm(orc.concat(gathered[:rows], nb), p.w)
+            if last:
+                orc.scale(z, p.alpha)
+            else:
+                v = orc.rebin(z, p.t_mm)
+            work += deg_rows * k_in + rows * 2 * k_in * m
+        secs += time.perf_counter() - t
+    return work / secs, secs, orc.max_threads()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: the "
+                    "232,965-node Reddit-shaped 2-layer GCN the roofline target is stated on)")
+    ap.add_argument("--cpu-rows", type=int, default=16384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2305_02522_amd import binding as B
+    from paper_2305_02522_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    wl = W.make_workload(args.config)
+    log(f"workload cfg{args.config} {wl.name}: N={wl.n} raw pairs={len(wl.src)} "
+        f"({time.perf_counter() - t0:.1f}s)")
+    ctx = B.Context(0)
+    src = torch.as_tensor(wl.src, device="cuda")
+    dst = torch.as_tensor(wl.dst, device="cuda")
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    adj = B.adj_build(ctx, src, dst, len(wl.src), wl.n, wl.adj_flags)
+    build_ms = (time.perf_counter() - t1) * 1e3
+    del src, dst
+    log(f"adjacency: nnz={adj.nnz} max_degree={adj.max_degree} build {build_ms:.1f} ms")
+    model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
+    x = torch.as_tensor(wl.x, device="cuda").to(torch.float32)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        model.forward_ops(x)
+    torch.cuda.synchronize()
+
+    # timed region: K steps, one HIP event before every kernel launch (torch's current
+    # stream is the stream the library launches on)
+    labels, events = [], []
+
+    def mark(label):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        events[-1].append(ev)
+        if len(events) == 1:
+            labels.append(label)
+
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        events.append([])
+        model.forward_ops(x, mark)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+
+    per_op = {lab: [] for lab in labels if lab}
+    step_ms = []
+    for evs in events:
+        step_ms.append(evs[0].elapsed_time(evs[-1]))
+        for i, lab in enumerate(labels[:-1]):
+            per_op[lab].append(evs[i].elapsed_time(evs[i + 1]))
+    ms_per_step = wall_ms / args.steps
+    models = op_models(wl, adj.nnz)
+    total_work = sum(m["work"] for m in models.values())
+    value = total_work / (ms_per_step * 1e-3) / 1e9
+
+    kernels = {}
+    for lab, ts in per_op.items():
+        avg = float(np.mean(ts))
+        m = models[lab]
+        k = dict(avg_us=round(avg * 1e3, 2), min_us=round(float(np.min(ts)) * 1e3, 2),
+                 alg_MB=round(m["bytes"] / 1e6, 2),
+                 hbm_frac=round(m["bytes"] / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+        if m["work"]:
+            k["Gbit_ops_per_s"] = round(m["work"] / (avg * 1e-3) / 1e9, 1)
+        if "lane_ops" in m:
+            k["valu_frac"] = round(m["lane_ops"] / (avg * 1e-3) / 1e12 / VALU_PEAK_TLOPS, 4)
+        kernels[lab] = k
+    dom = max(per_op, key=lambda lab: np.mean(per_op[lab]))
+    dm, davg = models[dom], float(np.mean(per_op[dom])) * 1e-3
+    if dm["bound"] == "hbm":
+        ach = dm["bytes"] / davg / 1e9
+        roofline = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4), traffic=None)
+    else:
+        ach = dm["lane_ops"] / davg / 1e12
+        roofline = dict(kernel=dom, bound="alu", achieved=round(ach, 2),
+                        peak=round(VALU_PEAK_TLOPS, 2), unit="Tlane-op/s",
+                        frac=round(ach / VALU_PEAK_TLOPS, 4), traffic=None)
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        tr = json.load(open(traffic_file)).get(f"cfg{args.config}", {}).get(dom)
+        roofline["traffic"] = tr
+
+    result = {
+        "metric": "binary GNN layer throughput (Gbit-edge-ops/s) + full-graph inference ms, 1 GPU",
+        "value": round(value, 1), "unit": "Gbit-edge-ops/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64 bit-packed / int32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{args.config} {wl.name}: {len(wl.layers)}-layer binary "
+                               f"{wl.model.upper()}, N={wl.n}, nnz={adj.nnz}, dims={wl.dims}",
+                   "inference_ms_event_median": round(float(np.median(step_ms)), 4),
+                   "adj_build_ms": round(build_ms, 1), "bit_ops_per_step": total_work},
+        "kernels": kernels, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a row sample ...")
+        rate, secs, threads = cpu_baseline(wl, args.cpu_rows)
+        result["cpu_baseline"] = {
+            "value": round(rate / 1e9, 3), "unit": "Gbit-edge-ops/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"every step of the model on the first {min(args.cpu_rows, wl.n)} nodes "
+                      f"({secs:.1f} s of oracle time)"}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

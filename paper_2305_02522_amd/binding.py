@@ -300,3 +300,49 @@ class BinaryGNN:
                     sage_layer(ctx, adj, a, p["k_in"], p["wb"], p["m"], p["wb"].stride(0),
                                p["t_agg"], p["t_mm"], nxt, nxt.stride(0))
         return self.logits
+
+    def forward_ops(self, x_f32: torch.Tensor, mark=None) -> torch.Tensor:
+        """Same kernels as forward(), enqueued one low-level entry point at a time;
+        `mark(label)` is called before every call (the benchmark records a HIP event
+        there) and `mark(None)` after the last one."""
+        ctx, adj = self.ctx, self.adj
+        mark = mark or (lambda label: None)
+        n, k0 = x_f32.shape
+        a0 = self.act[0]
+        mark("pack_f32")
+        pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
+        nl = len(self.params)
+        for l, p in enumerate(self.params):
+            a = self.act[l]
+            last = l == nl - 1
+            wb, ws, m, kw, k_in = p["wb"], p["wb"].stride(0), p["m"], p["kw"], p["k_in"]
+            if self.model == "gcn":
+                if last:
+                    mark(f"L{l}.bgemm")
+                    bgemm(ctx, a, n, a.stride(0), k_in, kw, wb, m, ws, EPI_RAW_I32, None, None,
+                          self.tmp_i32, m)
+                    mark(f"L{l}.spmm_i32")
+                    spmm_i32(ctx, adj, self.tmp_i32, m, m, k_in, p["alpha"], self.logits,
+                             self.logits.stride(0))
+                else:
+                    nxt = self.act[l + 1]
+                    mw = words(m)
+                    mark(f"L{l}.bgemm")
+                    bgemm(ctx, a, n, a.stride(0), k_in, kw, wb, m, ws, EPI_THRESH_BITS, p["t_mm"],
+                          None, self.tmp_bits, mw)
+                    mark(f"L{l}.bspmm")
+                    bspmm(ctx, adj, self.tmp_bits, m, mw, EPI_THRESH_BITS, p["t_agg"], nxt,
+                          nxt.stride(0))
+            else:
+                mark(f"L{l}.bspmm")
+                bspmm(ctx, adj, a, k_in, 2 * kw, EPI_THRESH_BITS, p["t_agg"], a[:, kw:], 2 * kw)
+                mark(f"L{l}.bgemm")
+                if last:
+                    bgemm(ctx, a, n, 2 * kw, 2 * k_in, 2 * kw, wb, m, ws, EPI_SCALE_F32, None,
+                          p["alpha"], self.logits, self.logits.stride(0))
+                else:
+                    nxt = self.act[l + 1]
+                    bgemm(ctx, a, n, 2 * kw, 2 * k_in, 2 * kw, wb, m, ws, EPI_THRESH_BITS,
+                          p["t_mm"], None, nxt, nxt.stride(0))
+        mark(None)
+        return self.logits
