@@ -18,7 +18,10 @@
  *    race on.
  *  - every data pointer is a DEVICE pointer owned by the caller and must stay
  *    valid until the enqueued work has run.  The library allocates device
- *    memory only inside a context (a few KB) and inside a bitgnn_adj.
+ *    memory only inside a bitgnn_adj and inside a context (a few KB, plus a
+ *    grow-only workspace for the blocked aggregation: 16 B per node and 160 B
+ *    per row part; it grows, with a device synchronization, the first time a
+ *    larger graph is aggregated, never afterwards).
  *  - packed bit layout (part of the ABI): a packed matrix is row-major
  *    uint64 words, little endian; logical bit k of a row is bit (k % 64) of
  *    word (k / 64); bit 1 encodes +1 and bit 0 encodes -1.  Rows are addressed
@@ -74,6 +77,16 @@ void bitgnn_ctx_destroy(bitgnn_ctx *ctx);
 /* Message of the most recent failing call on `ctx` ("" if none).  The string
  * is owned by the context and valid until the next call on it. */
 const char *bitgnn_last_error(const bitgnn_ctx *ctx);
+
+/* Tuning of the aggregation format built by later bitgnn_adj_build calls (the
+ * counterpart of the paper's tuning utilities, Section 3.4).  A graph with at
+ * least min_avg_degree stored non-zeros per node also gets a column-blocked form
+ * whose activation blocks of cb_nodes nodes (64..8192) are staged in LDS and
+ * whose rows are cut into parts of at most part_len (4..1023) neighbours;
+ * sparser graphs use plain CSR with global-memory gathers.  Results do not depend
+ * on these values.  Defaults: 8192, 512, 32. */
+int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
+                          int32_t min_avg_degree);
 
 /* ---- BIN: binarize and pack (Section 2.2 sign rule; Section 2.3) --------- */
 

@@ -44,6 +44,7 @@ _SIGNATURES = {
     "bitgnn_ctx_create": (_int, [ctypes.POINTER(_vp), _int]),
     "bitgnn_ctx_destroy": (None, [_vp]),
     "bitgnn_last_error": (ctypes.c_char_p, [_vp]),
+    "bitgnn_ctx_set_tuning": (_int, [_vp, _i32, _i32, _i32]),
     "bitgnn_pack_f32": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _vp, _i64]),
     "bitgnn_pack_i8": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _i64]),
     "bitgnn_pack_weights_i8": (_int, [_vp, _vp, _vp, _i32, _i32, _i64, _vp, _i64]),
@@ -155,6 +156,10 @@ def words(k: int) -> int:
 
 
 # --- one function per C entry point ----------------------------------------
+
+def ctx_set_tuning(ctx: Context, cb_nodes: int, part_len: int, min_avg_degree: int):
+    ctx.check(_lib.bitgnn_ctx_set_tuning(ctx.handle, cb_nodes, part_len, min_avg_degree))
+
 
 def pack_f32(ctx: Context, x, n, K, ldx, tau, out, out_stride):
     ctx.check(_lib.bitgnn_pack_f32(ctx.handle, _stream(), _ptr(x), n, K, ldx, _ptr(tau), _ptr(out),

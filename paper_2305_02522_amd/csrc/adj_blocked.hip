@@ -1,0 +1,343 @@
+// Column-blocked, length-balanced form of the adjacency for the LDS-staged
+// bit-SpMM (the role of the paper's fine-representing / dynamic-coarsening
+// scheme, Section 3.2.1: store the sparse bit matrix finely, coarsen on chip).
+//
+// Why: a 16-byte activation row gathered from global memory costs a whole
+// 128-byte cache line (measured ~0.33 gathers/clock/CU on MI355X), while the
+// same gather from LDS runs ~11x faster.  So the activation matrix is cut into
+// column blocks of `cbn` nodes that fit the 160 KB LDS, and the adjacency is
+// stored so that a workgroup streams, per column block, only 16-bit column ids
+// local to the block.
+//
+// Layout decisions
+//  - nodes are renumbered by decreasing degree ("slot"), so that hub columns
+//    share the first blocks and rows of similar length sit together;
+//  - a row's neighbour list (sorted by column slot) is cut into parts of at
+//    most `part_len` entries ("virtual rows"): a hub row becomes many parts,
+//    each touching one or two column blocks; partial counts are merged later.
+//    This bounds the work of one lane, which balances wavefronts on a
+//    power-law graph;
+//  - parts are ordered by (first block, last block, length); 64 consecutive
+//    parts form a slice (one wavefront, one part per lane), 16 slices a
+//    workgroup.  For every (slice, block) tile the ids are stored lane-
+//    interleaved in groups of 4 steps: group g holds idx16[(g*64+lane)*4+k],
+//    padded with the id `cbn`, which addresses an all-zero LDS row.
+#include "prims.h"
+
+#include <stdlib.h>
+
+namespace {
+
+constexpr uint32_t kVidMask = (1u << 30) - 1;
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(v, d, 64);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(v, d, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// slot numbering, degrees in slot order, parts per row
+__global__ void slot_kernel(const int32_t *__restrict__ order, const int32_t *__restrict__ deg,
+                            uint32_t n, int part_len, int32_t *__restrict__ rank,
+                            uint32_t *__restrict__ deg_sorted, uint32_t *__restrict__ nparts)
+{
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s > n)
+        return;
+    if (s == n) { // terminators of the two scans
+        deg_sorted[n] = 0;
+        nparts[n] = 0;
+        return;
+    }
+    const int32_t i = order[s];
+    rank[i] = (int32_t)s;
+    const uint32_t d = (uint32_t)deg[i];
+    deg_sorted[s] = d;
+    const uint32_t np = (d + part_len - 1) / part_len;
+    nparts[s] = np ? np : 1u;
+}
+
+// keys (row slot << cbits | column slot), one wavefront per row
+__global__ __launch_bounds__(256) void blocked_keys_kernel(
+    const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
+    const int32_t *__restrict__ order, const int32_t *__restrict__ rank,
+    const uint32_t *__restrict__ rp2, uint32_t n, int cbits, uint64_t *__restrict__ keys)
+{
+    const uint32_t s = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (s >= n)
+        return;
+    const int32_t i = order[s];
+    const uint32_t beg = rowptr[i], d = rowptr[i + 1] - beg, o = rp2[s];
+    for (uint32_t k = lane; k < d; k += 64)
+        keys[o + k] = ((uint64_t)s << cbits) | (uint32_t)rank[col[beg + k]];
+}
+
+// part descriptors and their sort keys
+__global__ void vrow_kernel(const uint64_t *__restrict__ skeys, const uint32_t *__restrict__ rp2,
+                            const uint32_t *__restrict__ vptr, uint32_t n, int cbits, int cbn,
+                            uint32_t *__restrict__ v_beg, uint32_t *__restrict__ v_end,
+                            uint64_t *__restrict__ vkeys)
+{
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n)
+        return;
+    const uint64_t mask = (1ull << cbits) - 1;
+    const uint32_t r0 = rp2[s], d = rp2[s + 1] - r0;
+    const uint32_t v0 = vptr[s], np = vptr[s + 1] - v0;
+    const uint32_t plen = (d + np - 1) / np; // np >= 1
+    for (uint32_t p = 0; p < np; ++p) {
+        const uint32_t b = r0 + min(d, p * plen), e = r0 + min(d, (p + 1) * plen);
+        const uint32_t len = e - b;
+        const uint64_t lo = len ? (skeys[b] & mask) / (uint32_t)cbn : 0;
+        const uint64_t hi = len ? (skeys[e - 1] & mask) / (uint32_t)cbn : 0;
+        const uint32_t v = v0 + p;
+        v_beg[v] = b;
+        v_end[v] = e;
+        vkeys[v] = (lo << 52) | (hi << 40) | ((uint64_t)(1023u - len) << 30) | v;
+    }
+}
+
+// per slice: range of column blocks its parts touch
+__global__ __launch_bounds__(64) void slice_range_kernel(const uint64_t *__restrict__ svkeys,
+                                                         uint32_t V, uint32_t S,
+                                                         uint32_t *__restrict__ sl_cb,
+                                                         uint32_t *__restrict__ sl_ntiles)
+{
+    const uint32_t slice = blockIdx.x;
+    const int lane = threadIdx.x;
+    if (slice == S) { // scan terminator
+        if (lane == 0)
+            sl_ntiles[S] = 0;
+        return;
+    }
+    const uint32_t pos = slice * 64 + lane;
+    const bool valid = pos < V;
+    const uint64_t key = valid ? svkeys[pos] : 0;
+    const uint32_t lo = wave_min_u32(valid ? (uint32_t)(key >> 52) : 0xFFFu);
+    const uint32_t hi = wave_max_u32(valid ? (uint32_t)(key >> 40) & 0xFFFu : 0u);
+    if (lane == 0) {
+        sl_cb[slice] = lo | (hi << 16);
+        sl_ntiles[slice] = hi - lo + 1;
+    }
+}
+
+// per (slice, block) tile: steps = longest lane; FILL = false counts groups,
+// FILL = true writes the lane-interleaved ids
+template <bool FILL>
+__global__ __launch_bounds__(64) void tile_kernel(
+    const uint64_t *__restrict__ svkeys, uint32_t V, const uint32_t *__restrict__ v_beg,
+    const uint32_t *__restrict__ v_end, const uint64_t *__restrict__ skeys, int cbits, int cbn,
+    const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
+    uint32_t *__restrict__ tile_group, uint16_t *__restrict__ idx16)
+{
+    const uint32_t slice = blockIdx.x;
+    const int lane = threadIdx.x;
+    const uint32_t pos = slice * 64 + lane;
+    const uint64_t mask = (1ull << cbits) - 1;
+    uint32_t ptr = 0, e = 0;
+    if (pos < V) {
+        const uint32_t v = (uint32_t)svkeys[pos] & kVidMask;
+        ptr = v_beg[v];
+        e = v_end[v];
+    }
+    const uint32_t lo = sl_cb[slice] & 0xFFFFu, hi = sl_cb[slice] >> 16;
+    const uint32_t t0 = sl_tile_base[slice];
+    for (uint32_t cb = lo; cb <= hi; ++cb) {
+        const uint64_t lim = (uint64_t)(cb + 1) * (uint32_t)cbn;
+        const uint32_t first = ptr;
+        while (ptr < e && (skeys[ptr] & mask) < lim)
+            ++ptr;
+        const uint32_t cnt = ptr - first;
+        if (!FILL) {
+            const uint32_t m = wave_max_u32(cnt);
+            if (lane == 0)
+                tile_group[t0 + cb - lo] = (m + 3) / 4;
+        } else {
+            const uint32_t g0 = tile_group[t0 + cb - lo];
+            const uint32_t steps = (tile_group[t0 + cb - lo + 1] - g0) * 4;
+            for (uint32_t k = 0; k < steps; ++k) {
+                const uint32_t id =
+                    k < cnt ? (uint32_t)((skeys[first + k] & mask) - (uint64_t)cb * (uint32_t)cbn)
+                            : (uint32_t)cbn;
+                idx16[((uint64_t)(g0 + k / 4) * 64 + lane) * 4 + (k & 3)] = (uint16_t)id;
+            }
+        }
+    }
+}
+
+__global__ void part_pos_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
+                                uint32_t *__restrict__ part_pos)
+{
+    const uint32_t pos = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos < V)
+        part_pos[(uint32_t)svkeys[pos] & kVidMask] = pos;
+}
+
+__global__ void wg_range_kernel(const uint32_t *__restrict__ sl_cb, uint32_t S, uint32_t W,
+                                uint32_t *__restrict__ wg_cb)
+{
+    const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W)
+        return;
+    uint32_t lo = 0xFFFFu, hi = 0;
+    for (uint32_t s = w * 16; s < w * 16 + 16 && s < S; ++s) {
+        lo = min(lo, sl_cb[s] & 0xFFFFu);
+        hi = max(hi, sl_cb[s] >> 16);
+    }
+    wg_cb[w] = lo | (hi << 16);
+}
+
+} // namespace
+
+void bg_free_blocked(bitgnn_blocked *b)
+{
+    if (!b)
+        return;
+    (void)hipFree(b->wg_cb);
+    (void)hipFree(b->sl_cb);
+    (void)hipFree(b->sl_tile_base);
+    (void)hipFree(b->tile_group);
+    (void)hipFree(b->idx16);
+    (void)hipFree(b->row_vptr);
+    (void)hipFree(b->part_pos);
+    free(b);
+}
+
+// Builds adj->blk from the CSR arrays of `adj` (already on the device).
+int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
+{
+    const uint32_t n = (uint32_t)adj->n, nnz = (uint32_t)adj->nnz;
+    const int cbn = ctx->cb_nodes, part_len = ctx->part_len;
+    const int64_t ncb = (adj->n + cbn - 1) / cbn;
+    if (ncb > 4095 || nnz == 0)
+        return BITGNN_OK; // stays on the CSR path
+    int cbits = 1;
+    while ((1ll << cbits) < adj->n)
+        ++cbits;
+
+    DevBuf rank, deg_sorted, nparts, keys_a, keys_b, hist, scan_ws;
+    const uint32_t sort_n = nnz > n ? nnz : n;
+    const uint32_t sort_tiles = (sort_n + kSortTile - 1) / kSortTile;
+    BG_HIP(ctx, rank.alloc((size_t)n * 4));
+    BG_HIP(ctx, deg_sorted.alloc(((size_t)n + 1) * 4));
+    BG_HIP(ctx, nparts.alloc(((size_t)n + 1) * 4));
+    BG_HIP(ctx, keys_a.alloc((size_t)sort_n * 8));
+    BG_HIP(ctx, keys_b.alloc((size_t)sort_n * 8));
+    BG_HIP(ctx, hist.alloc((size_t)256 * sort_tiles * 4));
+    BG_HIP(ctx, scan_ws.alloc(scan_ws_words((uint64_t)256 * sort_tiles) * 4));
+
+    slot_kernel<<<blocks_for((int64_t)n + 1, 256), 256, 0, s>>>(
+        adj->order, adj->deg, n, part_len, rank.as<int32_t>(), deg_sorted.as<uint32_t>(),
+        nparts.as<uint32_t>());
+    // exclusive scans: rp2 = entry offsets by slot, vptr = first part by slot
+    scan_inplace(deg_sorted.as<uint32_t>(), n + 1, scan_ws.as<uint32_t>(), s);
+    scan_inplace(nparts.as<uint32_t>(), n + 1, scan_ws.as<uint32_t>(), s);
+    const uint32_t *rp2 = deg_sorted.as<uint32_t>();
+    uint32_t *vptr = nparts.as<uint32_t>();
+    blocked_keys_kernel<<<blocks_for(n, 4), 256, 0, s>>>(adj->rowptr, adj->col, adj->order,
+                                                        rank.as<int32_t>(), rp2, n, cbits,
+                                                        keys_a.as<uint64_t>());
+    BG_LAUNCH_CHECK(ctx, "blocked_keys");
+    uint64_t *skeys = radix_sort(keys_a.as<uint64_t>(), keys_b.as<uint64_t>(), nnz, 2 * cbits,
+                                 hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
+    BG_LAUNCH_CHECK(ctx, "blocked radix_sort");
+    uint32_t V = 0;
+    BG_HIP(ctx, hipMemcpyAsync(&V, vptr + n, 4, hipMemcpyDeviceToHost, s));
+    BG_HIP(ctx, hipStreamSynchronize(s));
+    if (V >= kVidMask)
+        return BITGNN_OK;
+
+    // parts, sorted by (first block, last block, decreasing length)
+    DevBuf v_beg, v_end, vk_a, vk_b;
+    BG_HIP(ctx, v_beg.alloc((size_t)V * 4));
+    BG_HIP(ctx, v_end.alloc((size_t)V * 4));
+    BG_HIP(ctx, vk_a.alloc((size_t)V * 8));
+    BG_HIP(ctx, vk_b.alloc((size_t)V * 8));
+    vrow_kernel<<<blocks_for(n, 256), 256, 0, s>>>(skeys, rp2, vptr, n, cbits, cbn,
+                                                  v_beg.as<uint32_t>(), v_end.as<uint32_t>(),
+                                                  vk_a.as<uint64_t>());
+    BG_LAUNCH_CHECK(ctx, "vrow");
+    // V <= nnz + n, so the histogram buffers sized for sort_n suffice when V <= sort_n;
+    // V can exceed sort_n only if n > nnz, i.e. never on the graphs that get here
+    if ((V + kSortTile - 1) / kSortTile > sort_tiles)
+        return BITGNN_OK;
+    uint64_t *svkeys = radix_sort(vk_a.as<uint64_t>(), vk_b.as<uint64_t>(), V, 64,
+                                  hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
+
+    const uint32_t S = (V + 63) / 64, W = (S + 15) / 16;
+    DevBuf sl_cb, sl_tile_base, wg_cb, part_pos;
+    BG_HIP(ctx, sl_cb.alloc((size_t)S * 4));
+    BG_HIP(ctx, sl_tile_base.alloc(((size_t)S + 1) * 4));
+    BG_HIP(ctx, wg_cb.alloc((size_t)W * 4));
+    BG_HIP(ctx, part_pos.alloc((size_t)V * 4));
+    slice_range_kernel<<<S + 1, 64, 0, s>>>(svkeys, V, S, sl_cb.as<uint32_t>(),
+                                            sl_tile_base.as<uint32_t>());
+    scan_inplace(sl_tile_base.as<uint32_t>(), S + 1, scan_ws.as<uint32_t>(), s);
+    uint32_t T = 0;
+    BG_HIP(ctx, hipMemcpyAsync(&T, sl_tile_base.as<uint32_t>() + S, 4, hipMemcpyDeviceToHost, s));
+    BG_HIP(ctx, hipStreamSynchronize(s));
+
+    DevBuf tile_group;
+    BG_HIP(ctx, tile_group.alloc(((size_t)T + 1) * 4));
+    BG_HIP(ctx, hipMemsetAsync(tile_group.as<uint32_t>() + T, 0, 4, s));
+    tile_kernel<false><<<S, 64, 0, s>>>(svkeys, V, v_beg.as<uint32_t>(), v_end.as<uint32_t>(),
+                                        skeys, cbits, cbn, sl_cb.as<uint32_t>(),
+                                        sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
+                                        nullptr);
+    BG_LAUNCH_CHECK(ctx, "tile count");
+    scan_inplace(tile_group.as<uint32_t>(), T + 1, scan_ws.as<uint32_t>(), s);
+    uint32_t G = 0;
+    BG_HIP(ctx, hipMemcpyAsync(&G, tile_group.as<uint32_t>() + T, 4, hipMemcpyDeviceToHost, s));
+    BG_HIP(ctx, hipStreamSynchronize(s));
+    if ((uint64_t)G * 256 >= (1ull << 32))
+        return BITGNN_OK;
+
+    DevBuf idx16;
+    BG_HIP(ctx, idx16.alloc((size_t)G * 256 * 2));
+    tile_kernel<true><<<S, 64, 0, s>>>(svkeys, V, v_beg.as<uint32_t>(), v_end.as<uint32_t>(), skeys,
+                                       cbits, cbn, sl_cb.as<uint32_t>(),
+                                       sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
+                                       idx16.as<uint16_t>());
+    BG_LAUNCH_CHECK(ctx, "tile fill");
+    part_pos_kernel<<<blocks_for(V, 256), 256, 0, s>>>(svkeys, V, part_pos.as<uint32_t>());
+    wg_range_kernel<<<blocks_for(W, 256), 256, 0, s>>>(sl_cb.as<uint32_t>(), S, W,
+                                                      wg_cb.as<uint32_t>());
+    BG_LAUNCH_CHECK(ctx, "wg_range");
+    BG_HIP(ctx, hipStreamSynchronize(s));
+
+    bitgnn_blocked *b = (bitgnn_blocked *)calloc(1, sizeof(bitgnn_blocked));
+    BG_REQUIRE(ctx, b, BITGNN_ERR_INVALID_ARG, "bitgnn_adj_build: out of host memory");
+    b->cbn = cbn;
+    b->ncb = (int32_t)ncb;
+    b->n_vrows = V;
+    b->n_slices = S;
+    b->n_wgs = W;
+    b->n_tiles = T;
+    b->n_groups = G;
+    b->device_bytes = (size_t)G * 512 + ((size_t)T + 1) * 4 + ((size_t)S * 2 + 1) * 4 +
+                      (size_t)W * 4 + ((size_t)n + 1) * 4 + (size_t)V * 4;
+    b->wg_cb = (uint32_t *)wg_cb.release();
+    b->sl_cb = (uint32_t *)sl_cb.release();
+    b->sl_tile_base = (uint32_t *)sl_tile_base.release();
+    b->tile_group = (uint32_t *)tile_group.release();
+    b->idx16 = (uint16_t *)idx16.release();
+    b->row_vptr = (uint32_t *)nparts.release();
+    b->part_pos = (uint32_t *)part_pos.release();
+    adj->blk = b;
+    adj->device_bytes += b->device_bytes;
+    return BITGNN_OK;
+}

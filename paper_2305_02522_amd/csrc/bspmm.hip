@@ -65,6 +65,42 @@ __global__ void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C, int3
     table[idx] = word;
 }
 
+// Epilogue of one (node, 32-channel word): `acc` holds the bit-sliced count (plus
+// the seed for THRESH_BITS) as an ordinary binary number in P planes.
+template <int P, int EPI>
+__device__ __forceinline__ void bspmm_epilogue(const uint32_t (&acc)[P], uint32_t deg, uint32_t row,
+                                               int w, int32_t W32, int32_t C,
+                                               void *__restrict__ out, int64_t out_stride)
+{
+    const uint32_t tail = (uint32_t)C - 32u * (uint32_t)w; // channels from this word on
+    if (EPI == BITGNN_EPI_THRESH_BITS) {
+        // bit-sliced (value >= R), R = BIAS + deg/2, scanned from the low plane up
+        const uint32_t R = (1u << (P - 1)) + (deg >> 1);
+        uint32_t ge = 0xFFFFFFFFu;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t rbit = 0u - ((R >> p) & 1u); // all ones if bit p of R is set
+            ge = (acc[p] & ge) | (~rbit & (acc[p] | ge));
+        }
+        if (tail < 32u)
+            ge &= (1u << tail) - 1u;
+        uint32_t *o = (uint32_t *)out + (int64_t)row * out_stride * 2;
+        o[w] = ge;
+        if (w == W32 - 1 && (W32 & 1))
+            o[W32] = 0u; // upper half of the last 64-bit word
+    } else {
+        int32_t *o = (int32_t *)out + (int64_t)row * out_stride + 32 * w;
+        const int nb = tail < 32u ? (int)tail : 32;
+        for (int b = 0; b < nb; ++b) {
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+                cnt |= ((acc[p] >> b) & 1u) << p;
+            o[b] = 2 * (int32_t)cnt - (int32_t)deg;
+        }
+    }
+}
+
 template <int P, int EPI>
 __global__ __launch_bounds__(kBlock) void bspmm_kernel(
     const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
@@ -147,33 +183,7 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
 
     if (!active)
         return;
-    const uint32_t tail = (uint32_t)C - 32u * (uint32_t)w; // channels from this word on
-    if (EPI == BITGNN_EPI_THRESH_BITS) {
-        // bit-sliced (value >= R), R = BIAS + deg/2, scanned from the low plane up
-        const uint32_t R = (1u << (P - 1)) + (deg >> 1);
-        uint32_t ge = 0xFFFFFFFFu;
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const uint32_t rbit = 0u - ((R >> p) & 1u); // all ones if bit p of R is set
-            ge = (acc[p] & ge) | (~rbit & (acc[p] | ge));
-        }
-        if (tail < 32u)
-            ge &= (1u << tail) - 1u;
-        uint32_t *o = (uint32_t *)out + (int64_t)row * out_stride * 2;
-        o[w] = ge;
-        if (w == W32 - 1 && (W32 & 1))
-            o[W32] = 0u; // upper half of the last 64-bit word
-    } else {
-        int32_t *o = (int32_t *)out + (int64_t)row * out_stride + 32 * w;
-        const int nb = tail < 32u ? (int)tail : 32;
-        for (int b = 0; b < nb; ++b) {
-            uint32_t cnt = 0;
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-                cnt |= ((acc[p] >> b) & 1u) << p;
-            o[b] = 2 * (int32_t)cnt - (int32_t)deg;
-        }
-    }
+    bspmm_epilogue<P, EPI>(acc, deg, row, w, W32, C, out, out_stride);
 }
 
 // Integer aggregation of the last GCN layer: a group of LPR lanes owns a node,
@@ -218,6 +228,203 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
             out, out_stride);
 }
 
+
+// ---------------------------------------------------------------------------
+// LDS-staged variant for dense-enough graphs (format: adj_blocked.hip).
+//
+// A workgroup of 16 wavefronts walks the column blocks its slices touch.  For a
+// block it copies the (degree-ordered) activation rows of the block's nodes into
+// LDS with coalesced 16-byte accesses; then every lane streams the 16-bit local
+// ids of ITS row part, lane-interleaved in memory (one 8-byte load = 4 ids),
+// gathers the 16-byte rows from LDS and adds them into bit-sliced counters of
+// 10 planes x 128 channels.  Parts never exceed 1023 entries, so 10 planes do.
+// Each lane writes its partial planes; the merge kernel adds the parts of a
+// node, applies the seed and the threshold (or unpacks the integers).
+constexpr int kPartPlanes = 10;
+constexpr int kBlkThreads = 1024;
+
+__global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_stride32,
+                                   const int32_t *__restrict__ order, uint32_t n, int w0,
+                                   int W32, uint4 *__restrict__ hperm)
+{
+    const uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= n)
+        return;
+    const uint32_t *r = h32 + (int64_t)order[slot] * h_stride32;
+    uint4 v;
+    v.x = w0 + 0 < W32 ? r[w0 + 0] : 0u;
+    v.y = w0 + 1 < W32 ? r[w0 + 1] : 0u;
+    v.z = w0 + 2 < W32 ? r[w0 + 2] : 0u;
+    v.w = w0 + 3 < W32 ? r[w0 + 3] : 0u;
+    hperm[slot] = v;
+}
+
+__global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
+    const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_cb,
+    const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
+    const uint32_t *__restrict__ tile_group, const uint2 *__restrict__ idx, uint32_t S,
+    uint32_t V, uint4 *__restrict__ partial)
+{
+    extern __shared__ uint4 hblk[]; // cbn rows + one all-zero row
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t slice = blockIdx.x * (kBlkThreads / 64) + wave;
+    const bool has = slice < S;
+    const uint32_t wcb = wg_cb[blockIdx.x];
+    const uint32_t wlo = wcb & 0xFFFFu, whi = wcb >> 16;
+    uint32_t mylo = 1, myhi = 0, t0 = 0;
+    if (has) {
+        const uint32_t c = sl_cb[slice];
+        mylo = c & 0xFFFFu;
+        myhi = c >> 16;
+        t0 = sl_tile_base[slice];
+    }
+    if (tid == 0)
+        hblk[cbn] = make_uint4(0u, 0u, 0u, 0u);
+
+    uint32_t acc[kPartPlanes][4], pend[kPartPlanes][4];
+#pragma unroll
+    for (int p = 0; p < kPartPlanes; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            acc[p][q] = 0u;
+            pend[p][q] = 0u;
+        }
+    uint32_t blk = 0; // groups of 4 steps consumed by this wavefront
+
+    for (uint32_t cb = wlo; cb <= whi; ++cb) {
+        __syncthreads(); // all wavefronts are done with the previous block
+        const uint32_t base = cb * cbn;
+        const uint32_t rows = n - base < cbn ? n - base : cbn;
+        for (uint32_t i = tid; i < rows; i += kBlkThreads)
+            hblk[i] = hperm[base + i];
+        __syncthreads();
+        if (cb >= mylo && cb <= myhi) { // wave-uniform
+            const uint32_t tile = t0 + cb - mylo;
+            uint32_t g = tile_group[tile];
+            const uint32_t g1 = tile_group[tile + 1];
+            uint2 nxt = make_uint2(0u, 0u);
+            if (g < g1)
+                nxt = idx[(uint64_t)g * 64 + lane];
+            for (; g < g1; ++g) {
+                const uint2 pk = nxt;
+                if (g + 1 < g1)
+                    nxt = idx[(uint64_t)(g + 1) * 64 + lane];
+                const uint4 v0 = hblk[pk.x & 0xFFFFu];
+                const uint4 v1 = hblk[pk.x >> 16];
+                const uint4 v2 = hblk[pk.y & 0xFFFFu];
+                const uint4 v3 = hblk[pk.y >> 16];
+                const uint32_t x0[4] = {v0.x, v0.y, v0.z, v0.w};
+                const uint32_t x1[4] = {v1.x, v1.y, v1.z, v1.w};
+                const uint32_t x2[4] = {v2.x, v2.y, v2.z, v2.w};
+                const uint32_t x3[4] = {v3.x, v3.y, v3.z, v3.w};
+                uint32_t carry[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t a2, b2;
+                    csa(acc[0][q], x0[q], x1[q], a2);
+                    csa(acc[0][q], x2[q], x3[q], b2);
+                    csa(acc[1][q], a2, b2, carry[q]); // weight 4
+                }
+                // binary-counter cascade: level p holds a parked carry iff bit (p-2) of blk
+#pragma unroll
+                for (int p = 2; p < kPartPlanes; ++p) {
+                    if (!((blk >> (p - 2)) & 1u)) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            pend[p][q] = carry[q];
+                        break;
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t nc;
+                        csa(acc[p][q], pend[p][q], carry[q], nc);
+                        carry[q] = nc;
+                    }
+                }
+                ++blk;
+            }
+        }
+    }
+
+    // fold the parked carries
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t carry = 0;
+#pragma unroll
+        for (int p = 2; p < kPartPlanes; ++p) {
+            const uint32_t pd = ((blk >> (p - 2)) & 1u) ? pend[p][q] : 0u;
+            uint32_t nc;
+            csa(acc[p][q], pd, carry, nc);
+            carry = nc;
+        }
+    }
+    const uint32_t pos = slice * 64 + lane;
+    if (has && pos < V) {
+#pragma unroll
+        for (int p = 0; p < kPartPlanes; ++p)
+            partial[(uint64_t)pos * kPartPlanes + p] =
+                make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
+    }
+}
+
+// 4 lanes per node (one per 32-channel word of the window): sum the node's parts.
+template <int P, int EPI>
+__global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
+    const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
+    const uint32_t *__restrict__ part_pos, const int32_t *__restrict__ order,
+    const int32_t *__restrict__ deg, uint32_t n, int win, int32_t C, int32_t W32,
+    const uint32_t *__restrict__ seeds, void *__restrict__ out, int64_t out_stride)
+{
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t slot = t >> 2;
+    const int q = t & 3;
+    const int w = win * 4 + q;
+    if (slot >= n || w >= W32)
+        return;
+    const uint32_t row = (uint32_t)order[slot];
+    const uint32_t d = (uint32_t)deg[row];
+    uint32_t acc[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((d & 1u) * P + p) * W32 + w] : 0u;
+    const uint32_t v1 = row_vptr[slot + 1];
+    for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
+        const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
+        uint32_t carry = 0;
+#pragma unroll
+        for (int p = 0; p < kPartPlanes; ++p) {
+            uint32_t nc;
+            csa(acc[p], pp[p * 4], carry, nc);
+            carry = nc;
+        }
+#pragma unroll
+        for (int p = kPartPlanes; p < P; ++p) {
+            const uint32_t nc = acc[p] & carry;
+            acc[p] ^= carry;
+            carry = nc;
+        }
+    }
+    bspmm_epilogue<P, EPI>(acc, d, row, w, W32, C, out, out_stride);
+}
+
+template <int P>
+void launch_merge_p(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
+                    int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
+                    int64_t out_stride)
+{
+    const bitgnn_blocked *b = adj->blk;
+    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
+    if (epilogue == BITGNN_EPI_THRESH_BITS)
+        bspmm_merge_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid, kBlock, 0, s>>>(
+            partial32, b->row_vptr, b->part_pos, adj->order, adj->deg, (uint32_t)adj->n, win, C,
+            W32, seeds, out, out_stride);
+    else
+        bspmm_merge_kernel<P, BITGNN_EPI_RAW_I32><<<grid, kBlock, 0, s>>>(
+            partial32, b->row_vptr, b->part_pos, adj->order, adj->deg, (uint32_t)adj->n, win, C,
+            W32, seeds, out, out_stride);
+}
+
 } // namespace
 
 int bg_check_bspmm(bitgnn_ctx *ctx, const bitgnn_adj *adj, const uint64_t *hbits, int32_t C,
@@ -249,24 +456,95 @@ int bg_check_bspmm(bitgnn_ctx *ctx, const bitgnn_adj *adj, const uint64_t *hbits
     return BITGNN_OK;
 }
 
+// Counter planes: need max_degree < 2^(P-2).  One of 12, 16, 20, 26.
+static int planes_for(const bitgnn_adj *adj)
+{
+    int P = 12;
+    while ((1ll << (P - 2)) <= adj->max_degree)
+        P += (P == 20) ? 6 : 4;
+    return P;
+}
+
+static int launch_seeds(bitgnn_ctx *ctx, hipStream_t s, int epilogue, const int32_t *T, int32_t C,
+                        int32_t W32, int P, const uint32_t **seeds)
+{
+    *seeds = nullptr;
+    if (epilogue != BITGNN_EPI_THRESH_BITS)
+        return BITGNN_OK;
+    const int entries = 2 * P * W32;
+    BG_REQUIRE(ctx, (size_t)entries <= ctx->seed_table_words, BITGNN_ERR_UNSUPPORTED,
+               "bitgnn_bspmm: seed table too small");
+    bspmm_seed_kernel<<<(entries + 127) / 128, 128, 0, s>>>(T, C, W32, P, ctx->seed_table);
+    BG_LAUNCH_CHECK(ctx, "bspmm_seed");
+    *seeds = ctx->seed_table;
+    return BITGNN_OK;
+}
+
+int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                            const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
+                            const int32_t *T, void *out, int64_t out_stride)
+{
+    const bitgnn_blocked *b = adj->blk;
+    const int32_t W32 = (C + 31) / 32;
+    const int P = planes_for(adj);
+    const uint32_t *seeds;
+    int rc = launch_seeds(ctx, s, epilogue, T, C, W32, P, &seeds);
+    if (rc != BITGNN_OK)
+        return rc;
+    const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
+    const size_t part_bytes = (size_t)b->n_vrows * kPartPlanes * 16;
+    rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
+    if (rc != BITGNN_OK)
+        return rc;
+    uint4 *hperm = (uint4 *)ctx->ws;
+    uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
+    const size_t lds = ((size_t)b->cbn + 1) * 16;
+    BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const uint32_t *h32 = (const uint32_t *)hbits;
+    for (int win = 0; win * 4 < W32; ++win) {
+        blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
+            h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm);
+        bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
+            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_cb, b->sl_cb, b->sl_tile_base,
+            b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+        BG_LAUNCH_CHECK(ctx, "bspmm_blk");
+        switch (P) {
+        case 12:
+            launch_merge_p<12>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
+                               out, out_stride);
+            break;
+        case 16:
+            launch_merge_p<16>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
+                               out, out_stride);
+            break;
+        case 20:
+            launch_merge_p<20>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
+                               out, out_stride);
+            break;
+        default:
+            launch_merge_p<26>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
+                               out, out_stride);
+            break;
+        }
+        BG_LAUNCH_CHECK(ctx, "bspmm_merge");
+    }
+    return BITGNN_OK;
+}
+
 int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint64_t *hbits,
                     int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
                     int64_t out_stride)
 {
+    if (adj->blk)
+        return bg_launch_bspmm_blocked(ctx, s, adj, hbits, C, h_stride, epilogue, T, out,
+                                       out_stride);
     const int32_t W32 = (C + 31) / 32;
-    // planes: need max_degree < 2^(P-2)
-    int P = 12;
-    while ((1ll << (P - 2)) <= adj->max_degree)
-        P += (P == 20) ? 6 : 4; // 12, 16, 20, 26
-    const uint32_t *seeds = nullptr;
-    if (epilogue == BITGNN_EPI_THRESH_BITS) {
-        const int entries = 2 * P * W32;
-        BG_REQUIRE(ctx, (size_t)entries <= ctx->seed_table_words, BITGNN_ERR_UNSUPPORTED,
-                   "bitgnn_bspmm: seed table too small");
-        bspmm_seed_kernel<<<(entries + 127) / 128, 128, 0, s>>>(T, C, W32, P, ctx->seed_table);
-        BG_LAUNCH_CHECK(ctx, "bspmm_seed");
-        seeds = ctx->seed_table;
-    }
+    const int P = planes_for(adj);
+    const uint32_t *seeds;
+    int rc0 = launch_seeds(ctx, s, epilogue, T, C, W32, P, &seeds);
+    if (rc0 != BITGNN_OK)
+        return rc0;
     const int64_t threads = adj->n * (int64_t)W32;
     const int64_t grid = (threads + kBlock - 1) / kBlock;
     BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm: N*C too large");

@@ -16,6 +16,33 @@ struct bitgnn_ctx {
     char err[256];
     uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
     size_t seed_table_words;
+    // tuning of the column-blocked aggregation format (bitgnn_ctx_set_tuning)
+    int32_t cb_nodes;       // nodes per LDS-resident column block (<= 8192)
+    int32_t part_len;       // longest run of neighbours one lane accumulates (<= 1023)
+    int32_t min_avg_degree; // graphs sparser than this keep the plain CSR path only
+    // grow-only device workspace of the blocked bit-SpMM (permuted activations,
+    // per-part partial counters)
+    void *ws;
+    size_t ws_bytes;
+};
+
+// Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
+struct bitgnn_blocked {
+    int32_t cbn;            // nodes per column block
+    int32_t ncb;            // column blocks
+    uint32_t n_vrows;       // V: row parts ("virtual rows")
+    uint32_t n_slices;      // ceil(V / 64)
+    uint32_t n_wgs;         // ceil(slices / 16)
+    uint32_t n_tiles;       // (slice, column block) tiles
+    uint32_t n_groups;      // groups of 4 gather steps over all tiles
+    uint32_t *wg_cb;        // [n_wgs] first column block | last << 16
+    uint32_t *sl_cb;        // [n_slices] first | last << 16
+    uint32_t *sl_tile_base; // [n_slices + 1]
+    uint32_t *tile_group;   // [n_tiles + 1] prefix of 4-step groups
+    uint16_t *idx16;        // [n_groups * 256] column ids inside the block; cbn = "none"
+    uint32_t *row_vptr;     // [n + 1] by degree-order slot: first part of the row
+    uint32_t *part_pos;     // [V] position of a part in the processing order
+    size_t device_bytes;
 };
 
 struct bitgnn_adj {
@@ -28,6 +55,7 @@ struct bitgnn_adj {
     int32_t *deg;     // [n]
     int32_t *order;   // [n] rows by decreasing degree
     size_t device_bytes;
+    bitgnn_blocked *blk; // null when the graph is too sparse for the blocked path
 };
 
 static inline int bitgnn_fail(bitgnn_ctx *ctx, int code, const char *fmt, ...)
@@ -87,6 +115,13 @@ int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const
 int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const int32_t *Z,
                        int32_t M, int64_t z_stride, const float *alpha, void *out,
                        int64_t out_stride);
+
+int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj);
+void bg_free_blocked(bitgnn_blocked *b);
+int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                            const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
+                            const int32_t *T, void *out, int64_t out_stride);
+int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes);
 
 // Argument validation of the public calls, shared with the layer drivers.
 int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,

@@ -14,6 +14,9 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
     if (!ctx)
         return BITGNN_ERR_INVALID_ARG;
     ctx->device = device;
+    ctx->cb_nodes = 8192;
+    ctx->part_len = 512;
+    ctx->min_avg_degree = 32;
     if (device >= 0) {
         int count = 0;
         hipError_t e = hipGetDeviceCount(&count);
@@ -40,7 +43,43 @@ extern "C" void bitgnn_ctx_destroy(bitgnn_ctx *ctx)
         return;
     if (ctx->seed_table)
         (void)hipFree(ctx->seed_table);
+    if (ctx->ws)
+        (void)hipFree(ctx->ws);
     free(ctx);
 }
 
 extern "C" const char *bitgnn_last_error(const bitgnn_ctx *ctx) { return ctx ? ctx->err : ""; }
+
+extern "C" int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
+                                     int32_t min_avg_degree)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, cb_nodes >= 64 && cb_nodes <= 8192 && part_len >= 4 && part_len <= 1023 &&
+                        min_avg_degree >= 0,
+               BITGNN_ERR_INVALID_ARG,
+               "bitgnn_ctx_set_tuning: cb_nodes=%d (64..8192) part_len=%d (4..1023) "
+               "min_avg_degree=%d (>= 0)",
+               cb_nodes, part_len, min_avg_degree);
+    ctx->cb_nodes = cb_nodes;
+    ctx->part_len = part_len;
+    ctx->min_avg_degree = min_avg_degree;
+    return BITGNN_OK;
+}
+
+// Grow-only workspace; not safe to call while the stream is being captured.
+int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->ws_bytes)
+        return BITGNN_OK;
+    if (ctx->ws) {
+        BG_HIP(ctx, hipDeviceSynchronize());
+        BG_HIP(ctx, hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    bytes = (bytes + (1u << 20)) & ~(size_t)((1u << 20) - 1);
+    BG_HIP(ctx, hipMalloc(&ctx->ws, bytes));
+    ctx->ws_bytes = bytes;
+    return BITGNN_OK;
+}

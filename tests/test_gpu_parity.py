@@ -26,6 +26,20 @@ def ctx(B):
     c.close()
 
 
+TUNINGS = {"default": (8192, 512, 32), "csr-only": (8192, 512, 1 << 30),
+           "blocked-small": (128, 16, 0), "blocked-long-parts": (64, 1023, 0),
+           "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0)}
+
+
+@pytest.fixture(params=list(TUNINGS))
+def tuned(request, B, ctx):
+    """Every aggregation test runs on the CSR path and on the column-blocked path
+    with several block / part sizes: results must not depend on the format."""
+    B.ctx_set_tuning(ctx, *TUNINGS[request.param])
+    yield request.param
+    B.ctx_set_tuning(ctx, *TUNINGS["default"])
+
+
 def dev(a):
     return torch.as_tensor(np.ascontiguousarray(a), device="cuda")
 
@@ -127,6 +141,14 @@ def test_adj_build_matches_set_definition(B, ctx, n, e, flags, seed):
     adj.close()
 
 
+def test_tuning_validation(B, ctx):
+    for bad in ((63, 512, 32), (8193, 512, 32), (8192, 3, 32), (8192, 1024, 32), (8192, 512, -1)):
+        with pytest.raises(B.BitgnnError) as e:
+            B.ctx_set_tuning(ctx, *bad)
+        assert e.value.code == B.ERR_INVALID_ARG
+    B.ctx_set_tuning(ctx, 8192, 512, 32)
+
+
 def test_adj_build_rejects_out_of_range(B, ctx):
     src = dev(np.array([0, 1, 5], dtype=np.int32))
     dst = dev(np.array([1, 2, 0], dtype=np.int32))
@@ -214,7 +236,7 @@ def _graph(B, ctx, n, e, flags, seed, hubs=0):
     (3000, 40000, 100, W.ADJ_SYMMETRIZE, 0), (5000, 100000, 128, SYM_LOOPS, 2),
     (2000, 30000, 256, SYM_LOOPS, 0), (1500, 9000, 500, W.ADJ_SYMMETRIZE, 0),
     (40000, 100000, 128, SYM_LOOPS, 1), (700, 300, 65, 0, 0)])
-def test_bspmm_raw_and_threshold(B, ctx, n, e, C, flags, hubs):
+def test_bspmm_raw_and_threshold(B, ctx, tuned, n, e, C, flags, hubs):
     adj, rp, col, r = _graph(B, ctx, n, e, flags, n + C, hubs)
     v = W.pm1(r, (n, C))
     s = orc.spmm_pm1(rp, col, v)
@@ -239,7 +261,7 @@ def test_bspmm_raw_and_threshold(B, ctx, n, e, C, flags, hubs):
     adj.close()
 
 
-def test_bspmm_star_graph_long_row(B, ctx):
+def test_bspmm_star_graph_long_row(B, ctx, tuned):
     # one row with 70,000 neighbours: needs the 20-plane counters
     n, C = 70001, 96
     src = np.zeros(n - 1, dtype=np.int32)
@@ -310,7 +332,7 @@ def _check_model(B, ctx, wl):
 @pytest.mark.parametrize("cfg,kw", [
     (1, {}), (1, {"zero_thresholds": True}), (2, {"n": 1 << 13}), (3, {"n": 20000}),
     (4, {"n": 6000, "mean_deg": 120.0}), (5, {"n": 50000, "mean_deg": 20.0})])
-def test_model_small(B, ctx, cfg, kw):
+def test_model_small(B, ctx, tuned, cfg, kw):
     _check_model(B, ctx, W.make_workload(cfg, **kw))
 
 
