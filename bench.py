@@ -145,7 +145,8 @@ def main():
     adj = B.adj_build(ctx, src, dst, len(wl.src), wl.n, wl.adj_flags)
     build_ms = (time.perf_counter() - t1) * 1e3
     del src, dst
-    log(f"adjacency: nnz={adj.nnz} max_degree={adj.max_degree} build {build_ms:.1f} ms")
+    log(f"adjacency: nnz={adj.nnz} max_degree={adj.max_degree} build {build_ms:.1f} ms "
+        f"blocked={adj.blocked_info()}")
     model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
     x = torch.as_tensor(wl.x, device="cuda").to(torch.float32)
     torch.cuda.synchronize()

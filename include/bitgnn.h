@@ -126,6 +126,12 @@ int bitgnn_adj_info(const bitgnn_adj *adj, int64_t *N, int64_t *nnz, int64_t *ma
  * [N+1], col int32 [nnz] (sorted inside each row), deg int32 [N]. */
 int bitgnn_adj_csr(const bitgnn_adj *adj, const uint32_t **rowptr, const int32_t **col,
                    const int32_t **deg);
+/* Shape of the column-blocked form, if the handle has one (else every output is
+ * 0): row parts, slices of 64 parts, workgroups, (slice, block) tiles, stored ids
+ * including padding, and nodes per column block.  Any pointer may be NULL. */
+int bitgnn_adj_blocked_info(const bitgnn_adj *adj, int64_t *parts, int64_t *slices,
+                            int64_t *workgroups, int64_t *tiles, int64_t *stored_ids,
+                            int64_t *cb_nodes);
 void bitgnn_adj_destroy(bitgnn_adj *adj);
 
 /* ---- BMM: XNOR-popcount product (Section 2.2, +-1 bit-dot-product) ------- */

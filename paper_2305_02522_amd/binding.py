@@ -52,6 +52,7 @@ _SIGNATURES = {
     "bitgnn_adj_info": (_int, [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64),
                                ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_size_t)]),
     "bitgnn_adj_csr": (_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]),
+    "bitgnn_adj_blocked_info": (_int, [_vp] + [ctypes.POINTER(_i64)] * 6),
     "bitgnn_adj_destroy": (None, [_vp]),
     "bitgnn_bgemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _i32, _i64, _int, _vp,
                             _vp, _vp, _i64]),
@@ -133,6 +134,12 @@ class Adjacency:
         _lib.bitgnn_adj_info(handle, ctypes.byref(n), ctypes.byref(nnz), ctypes.byref(md),
                              ctypes.byref(nb))
         self.n, self.nnz, self.max_degree, self.device_bytes = n.value, nnz.value, md.value, nb.value
+
+    def blocked_info(self) -> dict:
+        v = [_i64() for _ in range(6)]
+        _lib.bitgnn_adj_blocked_info(self.handle, *[ctypes.byref(x) for x in v])
+        keys = ("parts", "slices", "workgroups", "tiles", "stored_ids", "cb_nodes")
+        return {k: x.value for k, x in zip(keys, v)}
 
     def csr_pointers(self):
         rp, col, deg = _vp(), _vp(), _vp()

@@ -287,6 +287,28 @@ extern "C" int bitgnn_adj_csr(const bitgnn_adj *adj, const uint32_t **rowptr, co
     return BITGNN_OK;
 }
 
+extern "C" int bitgnn_adj_blocked_info(const bitgnn_adj *adj, int64_t *parts, int64_t *slices,
+                                       int64_t *workgroups, int64_t *tiles, int64_t *stored_ids,
+                                       int64_t *cb_nodes)
+{
+    if (!adj)
+        return BITGNN_ERR_INVALID_ARG;
+    const bitgnn_blocked *b = adj->blk;
+    if (parts)
+        *parts = b ? b->n_vrows : 0;
+    if (slices)
+        *slices = b ? b->n_slices : 0;
+    if (workgroups)
+        *workgroups = b ? b->n_wgs : 0;
+    if (tiles)
+        *tiles = b ? b->n_tiles : 0;
+    if (stored_ids)
+        *stored_ids = b ? (int64_t)b->n_groups * 256 : 0;
+    if (cb_nodes)
+        *cb_nodes = b ? b->cbn : 0;
+    return BITGNN_OK;
+}
+
 extern "C" void bitgnn_adj_destroy(bitgnn_adj *adj)
 {
     if (!adj)

@@ -243,6 +243,43 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
 constexpr int kPartPlanes = 10;
 constexpr int kBlkThreads = 1024;
 
+constexpr int kPendTop = 6; // levels 2..5 park a carry; above, carries ripple (rare)
+
+// Adds a carry of weight 2^P0 into the counters.  Level p holds a parked carry iff
+// bit (p-2) of blk (the number of groups consumed so far): a binary counter, so
+// the control flow is wave-uniform and every register index is static.
+template <int P0>
+__device__ __forceinline__ void blk_cascade(uint32_t (&acc)[kPartPlanes][4],
+                                            uint32_t (&pend)[kPartPlanes][4],
+                                            uint32_t (&carry)[4], uint32_t blk)
+{
+    if constexpr (P0 < kPendTop) {
+        if (!((blk >> (P0 - 2)) & 1u)) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                pend[P0][q] = carry[q];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t nc;
+                csa(acc[P0][q], pend[P0][q], carry[q], nc);
+                carry[q] = nc;
+            }
+            blk_cascade<P0 + 1>(acc, pend, carry, blk);
+        }
+    } else {
+        // ripple the carry through the upper planes (once per 2^(kPendTop-2) groups)
+#pragma unroll
+        for (int p = kPendTop; p < kPartPlanes; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t nc = acc[p][q] & carry[q];
+                acc[p][q] ^= carry[q];
+                carry[q] = nc;
+            }
+    }
+}
+
 __global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_stride32,
                                    const int32_t *__restrict__ order, uint32_t n, int w0,
                                    int W32, uint4 *__restrict__ hperm)
@@ -326,34 +363,19 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
                     csa(acc[0][q], x2[q], x3[q], b2);
                     csa(acc[1][q], a2, b2, carry[q]); // weight 4
                 }
-                // binary-counter cascade: level p holds a parked carry iff bit (p-2) of blk
-#pragma unroll
-                for (int p = 2; p < kPartPlanes; ++p) {
-                    if (!((blk >> (p - 2)) & 1u)) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            pend[p][q] = carry[q];
-                        break;
-                    }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint32_t nc;
-                        csa(acc[p][q], pend[p][q], carry[q], nc);
-                        carry[q] = nc;
-                    }
-                }
+                blk_cascade<2>(acc, pend, carry, blk);
                 ++blk;
             }
         }
     }
 
-    // fold the parked carries
+    // fold the parked carries: planes become an ordinary binary number
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         uint32_t carry = 0;
 #pragma unroll
         for (int p = 2; p < kPartPlanes; ++p) {
-            const uint32_t pd = ((blk >> (p - 2)) & 1u) ? pend[p][q] : 0u;
+            const uint32_t pd = (p < kPendTop && ((blk >> (p - 2)) & 1u)) ? pend[p][q] : 0u;
             uint32_t nc;
             csa(acc[p][q], pd, carry, nc);
             carry = nc;
