@@ -45,12 +45,14 @@ def op_models(wl, nnz):
         if wl.model == "gcn":
             kw = w64(k_in)
             out_b = 4 * n * m if last else 8 * n * w64(m)
-            ops[f"L{l}.bgemm"] = dict(work=n * k_in * m, bytes=8 * kw * (n + m) + out_b,
-                                      lane_ops=2 * n * m * ((k_in + 31) // 32), bound="alu")
             if last:
-                ops[f"L{l}.spmm_i32"] = dict(work=nnz * m, bytes=idx_bytes + 8 * n * m,
-                                             bound="hbm")
+                # transform + aggregate + scale in one driver call
+                ops[f"L{l}.out_layer"] = dict(work=n * k_in * m + nnz * m,
+                                              bytes=idx_bytes + 8 * n * kw + 8 * kw * m + 4 * n
+                                              + 4 * n * m, bound="hbm")
             else:
+                ops[f"L{l}.bgemm"] = dict(work=n * k_in * m, bytes=8 * kw * (n + m) + out_b,
+                                          lane_ops=2 * n * m * ((k_in + 31) // 32), bound="alu")
                 ops[f"L{l}.bspmm"] = dict(work=nnz * m,
                                           bytes=idx_bytes + 16 * n * w64(m) + 4 * n + 4 * m,
                                           bound="hbm")

@@ -330,12 +330,10 @@ class BinaryGNN:
             wb, ws, m, kw, k_in = p["wb"], p["wb"].stride(0), p["m"], p["kw"], p["k_in"]
             if self.model == "gcn":
                 if last:
-                    mark(f"L{l}.bgemm")
-                    bgemm(ctx, a, n, a.stride(0), k_in, kw, wb, m, ws, EPI_RAW_I32, None, None,
-                          self.tmp_i32, m)
-                    mark(f"L{l}.spmm_i32")
-                    spmm_i32(ctx, adj, self.tmp_i32, m, m, k_in, p["alpha"], self.logits,
-                             self.logits.stride(0))
+                    # one call: the driver picks aggregate-then-transform when it can
+                    mark(f"L{l}.out_layer")
+                    gcn_out_layer(ctx, adj, a, a.stride(0), k_in, kw, wb, m, ws, p["alpha"],
+                                  self.tmp_i32, self.logits, self.logits.stride(0))
                 else:
                     nxt = self.act[l + 1]
                     mw = words(m)

@@ -35,9 +35,9 @@ constexpr int kGroup = 16; // neighbours per counter block
 // (acc, b, c) -> acc = sum bit, carry = majority
 __device__ __forceinline__ void csa(uint32_t &acc, uint32_t b, uint32_t c, uint32_t &carry)
 {
-    const uint32_t u = acc ^ b;
-    carry = (acc & b) | (u & c);
-    acc = u ^ c;
+    // v_bitop3_b32: any 3-input boolean in one VALU op (0xE8 majority, 0x96 xor3)
+    carry = __builtin_amdgcn_bitop3_b32(acc, b, c, 0xE8);
+    acc = __builtin_amdgcn_bitop3_b32(acc, b, c, 0x96);
 }
 
 // Seeds of the vertical counters: table[(e*P + p)*W32 + w] bit c' = bit p of
@@ -430,6 +430,80 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
     bspmm_epilogue<P, EPI>(acc, d, row, w, W32, C, out, out_stride);
 }
 
+// Output layer in aggregate-then-transform order, fused with the merge:
+//   logits[i][c] = alpha[c] * sum_k S[i][k] * w[k][c],  S = 2 cnt - deg  (K <= 128)
+// which equals the paper's MM.BBF + BSpMM.FBF order exactly in integers because no
+// non-linearity sits between the two products.  The counts never leave their
+// bit-sliced form: with b the weight bits of class c (w = 2b - 1),
+//   sum_k S_k w_kc = 4 A_c - 2 deg popc(b_c) - 2 B + deg K,
+//   A_c = sum_p 2^p popc(plane_p & b_c),  B = sum_p 2^p popc(plane_p).
+// 4 lanes per node, one 32-channel word each; quad sums via DPP.
+__device__ __forceinline__ int32_t quad_sum(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true); // lanes ^1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true); // lanes ^2
+    return v;
+}
+
+template <int P>
+__global__ __launch_bounds__(kBlock) void bspmm_merge_project_kernel(
+    const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
+    const uint32_t *__restrict__ part_pos, const int32_t *__restrict__ order,
+    const int32_t *__restrict__ deg, uint32_t n, int32_t K, int32_t W32,
+    const uint32_t *__restrict__ w32, int64_t w_stride32, int32_t M,
+    const float *__restrict__ alpha, float *__restrict__ out, int64_t ldo)
+{
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t slot_raw = t >> 2;
+    const int q = t & 3;
+    const bool live = slot_raw < n; // whole quads are live or dead together
+    const uint32_t slot = live ? slot_raw : 0u;
+    const bool has_word = live && q < W32;
+    const uint32_t row = (uint32_t)order[slot];
+    const int32_t d = deg[row];
+    uint32_t acc[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        acc[p] = 0u;
+    if (has_word) {
+        const uint32_t v1 = row_vptr[slot + 1];
+        for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
+            const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
+            uint32_t carry = 0;
+#pragma unroll
+            for (int p = 0; p < kPartPlanes; ++p) {
+                uint32_t nc;
+                csa(acc[p], pp[p * 4], carry, nc);
+                carry = nc;
+            }
+#pragma unroll
+            for (int p = kPartPlanes; p < P; ++p) {
+                const uint32_t nc = acc[p] & carry;
+                acc[p] ^= carry;
+                carry = nc;
+            }
+        }
+    }
+    int32_t bsum = 0;
+#pragma unroll
+    for (int p = P - 1; p >= 0; --p)
+        bsum = (bsum << 1) + __popc(acc[p]);
+    const int64_t B = quad_sum(bsum);
+    for (int c = 0; c < M; ++c) {
+        const uint32_t wq = q < W32 ? w32[(int64_t)c * w_stride32 + q] : 0u;
+        int32_t a = 0;
+#pragma unroll
+        for (int p = P - 1; p >= 0; --p)
+            a = (a << 1) + __popc(acc[p] & wq);
+        const int64_t A = quad_sum(a);
+        const int64_t pc = quad_sum(__popc(wq));
+        if (live && q == (c & 3)) {
+            const int64_t y = 4 * A - 2 * (int64_t)d * pc - 2 * B + (int64_t)d * K;
+            out[(int64_t)row * ldo + c] = alpha[c] * (float)(int32_t)y;
+        }
+    }
+}
+
 template <int P>
 void launch_merge_p(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
                     int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
@@ -551,6 +625,51 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
         }
         BG_LAUNCH_CHECK(ctx, "bspmm_merge");
     }
+    return BITGNN_OK;
+}
+
+// logits = alpha * ((A_hat v) W) through the blocked form (K <= 128).
+int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                                  const uint64_t *hbits, int32_t K, int64_t h_stride,
+                                  const uint64_t *wbits, int32_t M, int64_t w_stride,
+                                  const float *alpha, float *logits, int64_t ldo)
+{
+    const bitgnn_blocked *b = adj->blk;
+    const int32_t W32 = (K + 31) / 32;
+    const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
+    const size_t part_bytes = (size_t)b->n_vrows * kPartPlanes * 16;
+    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
+    if (rc != BITGNN_OK)
+        return rc;
+    uint4 *hperm = (uint4 *)ctx->ws;
+    uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
+    const size_t lds = ((size_t)b->cbn + 1) * 16;
+    BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
+        (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm);
+    bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
+        hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_cb, b->sl_cb, b->sl_tile_base,
+        b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+    BG_LAUNCH_CHECK(ctx, "bspmm_blk");
+    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
+    const uint32_t *w32 = (const uint32_t *)wbits;
+    // count planes only (no bias bit): max_degree < 2^P
+    int P = 12;
+    while ((1ll << P) <= adj->max_degree)
+        P += (P == 20) ? 6 : 4;
+#define BG_PROJECT(PP)                                                                            \
+    bspmm_merge_project_kernel<PP><<<grid, kBlock, 0, s>>>(                                      \
+        (const uint32_t *)partial, b->row_vptr, b->part_pos, adj->order, adj->deg,                \
+        (uint32_t)adj->n, K, W32, w32, w_stride * 2, M, alpha, logits, ldo)
+    switch (P) {
+    case 12: BG_PROJECT(12); break;
+    case 16: BG_PROJECT(16); break;
+    case 20: BG_PROJECT(20); break;
+    default: BG_PROJECT(26); break;
+    }
+#undef BG_PROJECT
+    BG_LAUNCH_CHECK(ctx, "bspmm_merge_project");
     return BITGNN_OK;
 }
 

@@ -122,6 +122,10 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
                             const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
                             const int32_t *T, void *out, int64_t out_stride);
 int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes);
+int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                                  const uint64_t *hbits, int32_t K, int64_t h_stride,
+                                  const uint64_t *wbits, int32_t M, int64_t w_stride,
+                                  const float *alpha, float *logits, int64_t ldo);
 
 // Argument validation of the public calls, shared with the layer drivers.
 int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,

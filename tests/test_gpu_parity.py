@@ -336,6 +336,46 @@ def test_model_small(B, ctx, tuned, cfg, kw):
     _check_model(B, ctx, W.make_workload(cfg, **kw))
 
 
+@pytest.mark.parametrize("n,e,K,M", [(300, 4000, 7, 3), (2000, 90000, 64, 41),
+                                     (5000, 200000, 128, 41), (3000, 150000, 100, 130)])
+def test_gcn_out_layer_both_orders(B, ctx, tuned, n, e, K, M):
+    """The output layer may aggregate first and transform second: same integers."""
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + K + M, hubs=1)
+    v = W.pm1(r, (n, K))
+    w = W.pm1(r, (K, M))
+    alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
+    ref = orc.gcn_out_layer(rp, col, v, w, alpha)
+    kw = (K + 63) // 64
+    tmp = torch.zeros((n, M), dtype=torch.int32, device="cuda")
+    out = torch.zeros((n, M + 2), dtype=torch.float32, device="cuda")
+    B.gcn_out_layer(ctx, adj, _pack_host(v), kw, K, kw, _pack_host(np.ascontiguousarray(w.T)), M,
+                    kw, dev(alpha), tmp, out, M + 2)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert rel_close(got[:, :M], ref)
+    assert np.all(got[:, M:] == 0)
+    # alpha = 1: logits are the exact integers
+    one = np.ones(M, dtype=np.float32)
+    B.gcn_out_layer(ctx, adj, _pack_host(v), kw, K, kw, _pack_host(np.ascontiguousarray(w.T)), M,
+                    kw, dev(one), tmp, out, M + 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy()[:, :M], orc.gcn_out_layer(rp, col, v, w, one))
+    adj.close()
+
+
+def test_forward_ops_equals_forward(B, ctx):
+    for cfg, kw in ((4, {"n": 6000, "mean_deg": 120.0}), (3, {"n": 20000})):
+        wl = W.make_workload(cfg, **kw)
+        adj = B.adj_build(ctx, dev(wl.src), dev(wl.dst), len(wl.src), wl.n, wl.adj_flags)
+        model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
+        x = dev(wl.x).to(torch.float32)
+        a = model.forward(x).clone()
+        b = model.forward_ops(x).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        adj.close()
+
+
 @pytest.mark.parametrize("cfg", [2, 3])
 def test_model_full_size(B, ctx, cfg):
     _check_model(B, ctx, W.make_workload(cfg))
