@@ -84,7 +84,7 @@ const char *bitgnn_last_error(const bitgnn_ctx *ctx);
  * whose activation blocks of cb_nodes nodes (64..8192) are staged in LDS and
  * whose rows are cut into parts of at most part_len (4..1023) neighbours;
  * sparser graphs use plain CSR with global-memory gathers.  Results do not depend
- * on these values.  Defaults: 8192, 512, 32. */
+ * on these values.  Defaults: 8192, 256, 32. */
 int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
                           int32_t min_avg_degree);
 

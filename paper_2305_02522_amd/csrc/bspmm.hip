@@ -296,18 +296,52 @@ __global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_s
     hperm[slot] = v;
 }
 
+// One group: 4 gathers of 16-byte rows from LDS, added into the bit-sliced counters.
+__device__ __forceinline__ void blk_consume(uint32_t i0, uint32_t i1, uint32_t i2, uint32_t i3,
+                                            const uint4 *hblk, uint32_t (&acc)[kPartPlanes][4],
+                                            uint32_t (&pend)[kPartPlanes][4], uint32_t blk)
+{
+    const uint4 v0 = hblk[i0];
+    const uint4 v1 = hblk[i1];
+    const uint4 v2 = hblk[i2];
+    const uint4 v3 = hblk[i3];
+    const uint32_t x0[4] = {v0.x, v0.y, v0.z, v0.w};
+    const uint32_t x1[4] = {v1.x, v1.y, v1.z, v1.w};
+    const uint32_t x2[4] = {v2.x, v2.y, v2.z, v2.w};
+    const uint32_t x3[4] = {v3.x, v3.y, v3.z, v3.w};
+    uint32_t carry[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t a2, b2;
+        csa(acc[0][q], x0[q], x1[q], a2);
+        csa(acc[0][q], x2[q], x3[q], b2);
+        csa(acc[1][q], a2, b2, carry[q]); // weight 4
+    }
+    blk_cascade<2>(acc, pend, carry, blk);
+}
+
+#ifdef BITGNN_PROFILE
+__device__ unsigned long long *g_blk_prof = nullptr; // per workgroup: start, end, fill, compute
+#define BLK_PROF_T() ((tid == 0) ? clock64() : 0)
+#endif
+
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
-    const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_cb,
-    const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
+    const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_order,
+    const uint32_t *__restrict__ wg_cb, const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
     const uint32_t *__restrict__ tile_group, const uint2 *__restrict__ idx, uint32_t S,
     uint32_t V, uint4 *__restrict__ partial)
 {
     extern __shared__ uint4 hblk[]; // cbn rows + one all-zero row
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t slice = blockIdx.x * (kBlkThreads / 64) + wave;
+#ifdef BITGNN_EXPERIMENT_NATURAL_ORDER
+    const uint32_t wg = blockIdx.x;
+#else
+    const uint32_t wg = wg_order[blockIdx.x]; // heaviest workgroups are dispatched first
+#endif
+    const uint32_t slice = wg * (kBlkThreads / 64) + wave;
     const bool has = slice < S;
-    const uint32_t wcb = wg_cb[blockIdx.x];
+    const uint32_t wcb = wg_cb[wg];
     const uint32_t wlo = wcb & 0xFFFFu, whi = wcb >> 16;
     uint32_t mylo = 1, myhi = 0, t0 = 0;
     if (has) {
@@ -328,14 +362,43 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             pend[p][q] = 0u;
         }
     uint32_t blk = 0; // groups of 4 steps consumed by this wavefront
+#ifdef BITGNN_PROFILE
+    const long long p_start = BLK_PROF_T();
+    const unsigned long long p_wall0 = (tid == 0) ? wall_clock64() : 0;
+    long long p_fill = 0, p_comp = 0, p_t0 = p_start;
+#endif
 
     for (uint32_t cb = wlo; cb <= whi; ++cb) {
         __syncthreads(); // all wavefronts are done with the previous block
+#ifdef BITGNN_PROFILE
+        { const long long t = BLK_PROF_T(); p_comp += t - p_t0; p_t0 = t; }
+#endif
         const uint32_t base = cb * cbn;
         const uint32_t rows = n - base < cbn ? n - base : cbn;
-        for (uint32_t i = tid; i < rows; i += kBlkThreads)
-            hblk[i] = hperm[base + i];
+        // cbn <= 8192: at most 8 rows per thread, in two batches of 4 loads in flight
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const uint32_t i0 = tid + (half * 4 + 0) * kBlkThreads;
+            const uint32_t i1 = tid + (half * 4 + 1) * kBlkThreads;
+            const uint32_t i2 = tid + (half * 4 + 2) * kBlkThreads;
+            const uint32_t i3 = tid + (half * 4 + 3) * kBlkThreads;
+            const uint4 st0 = hperm[base + (i0 < rows ? i0 : 0u)];
+            const uint4 st1 = hperm[base + (i1 < rows ? i1 : 0u)];
+            const uint4 st2 = hperm[base + (i2 < rows ? i2 : 0u)];
+            const uint4 st3 = hperm[base + (i3 < rows ? i3 : 0u)];
+            if (i0 < rows)
+                hblk[i0] = st0;
+            if (i1 < rows)
+                hblk[i1] = st1;
+            if (i2 < rows)
+                hblk[i2] = st2;
+            if (i3 < rows)
+                hblk[i3] = st3;
+        }
         __syncthreads();
+#ifdef BITGNN_PROFILE
+        { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
+#endif
         if (cb >= mylo && cb <= myhi) { // wave-uniform
             const uint32_t tile = t0 + cb - mylo;
             uint32_t g = tile_group[tile];
@@ -347,28 +410,24 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
                 const uint2 pk = nxt;
                 if (g + 1 < g1)
                     nxt = idx[(uint64_t)(g + 1) * 64 + lane];
-                const uint4 v0 = hblk[pk.x & 0xFFFFu];
-                const uint4 v1 = hblk[pk.x >> 16];
-                const uint4 v2 = hblk[pk.y & 0xFFFFu];
-                const uint4 v3 = hblk[pk.y >> 16];
-                const uint32_t x0[4] = {v0.x, v0.y, v0.z, v0.w};
-                const uint32_t x1[4] = {v1.x, v1.y, v1.z, v1.w};
-                const uint32_t x2[4] = {v2.x, v2.y, v2.z, v2.w};
-                const uint32_t x3[4] = {v3.x, v3.y, v3.z, v3.w};
-                uint32_t carry[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint32_t a2, b2;
-                    csa(acc[0][q], x0[q], x1[q], a2);
-                    csa(acc[0][q], x2[q], x3[q], b2);
-                    csa(acc[1][q], a2, b2, carry[q]); // weight 4
-                }
-                blk_cascade<2>(acc, pend, carry, blk);
+                blk_consume(pk.x & 0xFFFFu, pk.x >> 16, pk.y & 0xFFFFu, pk.y >> 16, hblk, acc, pend,
+                            blk);
                 ++blk;
             }
         }
     }
 
+#ifdef BITGNN_PROFILE
+    __syncthreads();
+    if (tid == 0 && g_blk_prof) {
+        const long long t = clock64();
+        p_comp += t - p_t0;
+        unsigned long long *o = g_blk_prof + 8ull * blockIdx.x;
+        o[0] = p_start; o[1] = t; o[2] = p_fill; o[3] = p_comp;
+        o[4] = p_wall0; o[5] = wall_clock64(); o[6] = __smid();
+        o[7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)); /* XCC_ID */
+    }
+#endif
     // fold the parked carries: planes become an ordinary binary number
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -523,6 +582,13 @@ void launch_merge_p(hipStream_t s, int epilogue, const bitgnn_adj *adj, const ui
 
 } // namespace
 
+#ifdef BITGNN_PROFILE
+extern "C" int bitgnn_debug_set_blk_profile(unsigned long long *buf)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_blk_prof), &buf, sizeof(buf));
+}
+#endif
+
 int bg_check_bspmm(bitgnn_ctx *ctx, const bitgnn_adj *adj, const uint64_t *hbits, int32_t C,
                    int64_t h_stride, int epilogue, const int32_t *T, const void *out,
                    int64_t out_stride)
@@ -602,7 +668,7 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
         blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
             h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm);
         bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
-            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_cb, b->sl_cb, b->sl_tile_base,
+            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
             b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
         BG_LAUNCH_CHECK(ctx, "bspmm_blk");
         switch (P) {
@@ -649,7 +715,7 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
         (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm);
     bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
-        hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_cb, b->sl_cb, b->sl_tile_base,
+        hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
         b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
     BG_LAUNCH_CHECK(ctx, "bspmm_blk");
     const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);

@@ -35,6 +35,7 @@ struct bitgnn_blocked {
     uint32_t n_wgs;         // ceil(slices / 16)
     uint32_t n_tiles;       // (slice, column block) tiles
     uint32_t n_groups;      // groups of 4 gather steps over all tiles
+    uint32_t *wg_order;     // [n_wgs] workgroups by decreasing estimated work
     uint32_t *wg_cb;        // [n_wgs] first column block | last << 16
     uint32_t *sl_cb;        // [n_slices] first | last << 16
     uint32_t *sl_tile_base; // [n_slices + 1]
