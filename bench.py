@@ -37,8 +37,10 @@ def op_models(wl, nnz):
     idx_bytes = 4 * nnz + 4 * (n + 1)       # the stored format is CSR: 4 B per non-zero
     ops = {}
     k0 = wl.dims[0]
-    ops["pack_f32"] = dict(work=0, bytes=4 * n * k0 + 8 * n * w64(k0), bound="hbm")
     nl = len(wl.layers)
+    fused_first = wl.model == "gcn" and nl > 1      # float features feed the first product
+    if not fused_first:
+        ops["pack_f32"] = dict(work=0, bytes=4 * n * k0 + 8 * n * w64(k0), bound="hbm")
     for l in range(nl):
         k_in, m = wl.dims[l], wl.dims[l + 1]
         last = l == nl - 1
@@ -50,9 +52,15 @@ def op_models(wl, nnz):
                 ops[f"L{l}.out_layer"] = dict(work=n * k_in * m + nnz * m,
                                               bytes=idx_bytes + 8 * n * kw + 8 * kw * m + 4 * n
                                               + 4 * n * m, bound="hbm")
+            elif l == 0:
+                ops[f"L{l}.bgemm_f32"] = dict(work=n * k_in * m,
+                                              bytes=4 * n * k_in + 8 * kw * m + out_b,
+                                              lane_ops=2 * n * m * ((k_in + 31) // 32),
+                                              bound="hbm")
             else:
                 ops[f"L{l}.bgemm"] = dict(work=n * k_in * m, bytes=8 * kw * (n + m) + out_b,
                                           lane_ops=2 * n * m * ((k_in + 31) // 32), bound="alu")
+            if not last:
                 ops[f"L{l}.bspmm"] = dict(work=nnz * m,
                                           bytes=idx_bytes + 16 * n * w64(m) + 4 * n + 4 * m,
                                           bound="hbm")

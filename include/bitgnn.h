@@ -152,6 +152,15 @@ int bitgnn_bgemm(bitgnn_ctx *ctx, void *stream, const uint64_t *xbits, int64_t n
                  int64_t w_stride, int epilogue, const int32_t *T, const float *alpha, void *out,
                  int64_t out_stride);
 
+/* The same product with full-precision activations, BIN folded in (the paper's
+ * BMM.FBB / BMM.FBF): vx[i][k] = +1 if x[i*ldx + k] >= tau[k] (tau NULL = 0) else -1,
+ * k < K; the packed activations are never materialized.  x: float [n][ldx];
+ * wbits: uint64 [M][w_stride], ceil(K/64) words used.  Epilogues as bitgnn_bgemm. */
+int bitgnn_bgemm_f32(bitgnn_ctx *ctx, void *stream, const float *x, int64_t n, int32_t K,
+                     int64_t ldx, const float *tau, const uint64_t *wbits, int32_t M,
+                     int64_t w_stride, int epilogue, const int32_t *T, const float *alpha,
+                     void *out, int64_t out_stride);
+
 /* ---- BSpMM: bit sparse product (Section 3.2.2; Algorithm 1) -------------- */
 
 /* S[i][c] = sum_{j in N(i)} v[j][c] = 2*#{j in N(i) : bit c of hbits_j} - deg(i)
@@ -186,8 +195,17 @@ int bitgnn_gcn_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const
                      int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits,
                      int32_t M, int64_t w_stride, const int32_t *T_mm, const int32_t *T_agg,
                      uint64_t *tmp_bits, uint64_t *out_bits, int64_t out_stride);
+/* First GCN layer on float features, the paper's BMM.FBB + BSpMM.BBB:
+ *   h = (bin(x) W >= T_mm) ; out = (A_hat h >= T_agg).  x: float [N][ldx]. */
+int bitgnn_gcn_layer_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const float *x,
+                         int32_t K, int64_t ldx, const float *tau, const uint64_t *wbits,
+                         int32_t M, int64_t w_stride, const int32_t *T_mm, const int32_t *T_agg,
+                         uint64_t *tmp_bits, uint64_t *out_bits, int64_t out_stride);
 /* GCN output layer, BMM.BBF + BSpMM.FBF with one scale at the end:
- *   logits = alpha * (A_hat (xbits W)).  tmp_i32: caller scratch int32 [N][M]. */
+ *   logits = alpha * (A_hat (xbits W)).  tmp_i32: caller scratch int32 [N][M].
+ * No non-linearity sits between the two products, so when the handle has the
+ * column-blocked form and K <= 128 the call evaluates (A_hat xbits) W instead: the
+ * same integers, aggregated on 1-bit rows. */
 int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                          const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
                          const uint64_t *wbits, int32_t M, int64_t w_stride, const float *alpha,

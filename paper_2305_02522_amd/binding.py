@@ -56,6 +56,10 @@ _SIGNATURES = {
     "bitgnn_adj_destroy": (None, [_vp]),
     "bitgnn_bgemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i32, _i32, _vp, _i32, _i64, _int, _vp,
                             _vp, _vp, _i64]),
+    "bitgnn_bgemm_f32": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _vp, _i32, _i64, _int, _vp,
+                                _vp, _vp, _i64]),
+    "bitgnn_gcn_layer_f32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _i32, _i64, _vp, _vp,
+                                    _vp, _vp, _i64]),
     "bitgnn_bspmm": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
     "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
     "bitgnn_gcn_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp, _vp,
@@ -196,6 +200,21 @@ def bgemm(ctx: Context, xbits, n, x_stride, K, kwords, wbits, M, w_stride, epilo
                                 out_stride))
 
 
+def bgemm_f32(ctx: Context, x, n, K, ldx, tau, wbits, M, w_stride, epilogue, T, alpha, out,
+              out_stride):
+    ctx.check(_lib.bitgnn_bgemm_f32(ctx.handle, _stream(), _ptr(x), n, K, ldx, _ptr(tau),
+                                    _ptr(wbits), M, w_stride, epilogue, _ptr(T), _ptr(alpha),
+                                    _ptr(out), out_stride))
+
+
+def gcn_layer_f32(ctx: Context, adj, x, K, ldx, tau, wbits, M, w_stride, T_mm, T_agg, tmp_bits,
+                  out_bits, out_stride):
+    ctx.check(_lib.bitgnn_gcn_layer_f32(ctx.handle, _stream(), adj.handle if adj else None,
+                                        _ptr(x), K, ldx, _ptr(tau), _ptr(wbits), M, w_stride,
+                                        _ptr(T_mm), _ptr(T_agg), _ptr(tmp_bits), _ptr(out_bits),
+                                        out_stride))
+
+
 def bspmm(ctx: Context, adj: Optional[Adjacency], hbits, C, h_stride, epilogue, T, out, out_stride):
     ctx.check(_lib.bitgnn_bspmm(ctx.handle, _stream(), adj.handle if adj else None, _ptr(hbits), C,
                                 h_stride, epilogue, _ptr(T), _ptr(out), out_stride))
@@ -288,8 +307,12 @@ class BinaryGNN:
         n, k0 = x_f32.shape
         assert n == self.n and k0 == self.dims[0]
         a0 = self.act[0]
-        pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
         nl = len(self.params)
+        # GCN with a hidden layer: the float features feed the first product directly
+        # (BMM.FBB); otherwise they are packed first.
+        fused_first = self.model == "gcn" and nl > 1
+        if not fused_first:
+            pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
         for l, p in enumerate(self.params):
             a = self.act[l]
             last = l == nl - 1
@@ -298,6 +321,11 @@ class BinaryGNN:
                     gcn_out_layer(ctx, adj, a, a.stride(0), p["k_in"], p["kw"], p["wb"], p["m"],
                                   p["wb"].stride(0), p["alpha"], self.tmp_i32, self.logits,
                                   self.logits.stride(0))
+                elif l == 0:
+                    nxt = self.act[l + 1]
+                    gcn_layer_f32(ctx, adj, x_f32, k0, x_f32.stride(0), None, p["wb"], p["m"],
+                                  p["wb"].stride(0), p["t_mm"], p["t_agg"], self.tmp_bits, nxt,
+                                  nxt.stride(0))
                 else:
                     nxt = self.act[l + 1]
                     gcn_layer(ctx, adj, a, a.stride(0), p["k_in"], p["kw"], p["wb"], p["m"],
@@ -321,9 +349,11 @@ class BinaryGNN:
         mark = mark or (lambda label: None)
         n, k0 = x_f32.shape
         a0 = self.act[0]
-        mark("pack_f32")
-        pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
         nl = len(self.params)
+        fused_first = self.model == "gcn" and nl > 1
+        if not fused_first:
+            mark("pack_f32")
+            pack_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, a0, a0.stride(0))
         for l, p in enumerate(self.params):
             a = self.act[l]
             last = l == nl - 1
@@ -337,9 +367,14 @@ class BinaryGNN:
                 else:
                     nxt = self.act[l + 1]
                     mw = words(m)
-                    mark(f"L{l}.bgemm")
-                    bgemm(ctx, a, n, a.stride(0), k_in, kw, wb, m, ws, EPI_THRESH_BITS, p["t_mm"],
-                          None, self.tmp_bits, mw)
+                    if l == 0:
+                        mark(f"L{l}.bgemm_f32")
+                        bgemm_f32(ctx, x_f32, n, k0, x_f32.stride(0), None, wb, m, ws,
+                                  EPI_THRESH_BITS, p["t_mm"], None, self.tmp_bits, mw)
+                    else:
+                        mark(f"L{l}.bgemm")
+                        bgemm(ctx, a, n, a.stride(0), k_in, kw, wb, m, ws, EPI_THRESH_BITS,
+                              p["t_mm"], None, self.tmp_bits, mw)
                     mark(f"L{l}.bspmm")
                     bspmm(ctx, adj, self.tmp_bits, m, mw, EPI_THRESH_BITS, p["t_agg"], nxt,
                           nxt.stride(0))

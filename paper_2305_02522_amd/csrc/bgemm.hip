@@ -98,6 +98,143 @@ __global__ __launch_bounds__(kWaves * 64) void bgemm_kernel(
     }
 }
 
+
+// BMM with full-precision activations (the paper's BMM.FBB / BMM.FBF, Section 3.1.2:
+// BIN folded into the product).  The binarization costs no pass of its own: 64 lanes
+// load 64 consecutive floats of a node row (one coalesced 256-byte access) and the
+// wave-wide compare mask IS the 64-bit activation word, already in scalar registers,
+// where the XOR with the lane's weight words wants it.  The packed activations are
+// never written to memory.  A wavefront owns TILES x 64 output channels, so the float
+// matrix is streamed from HBM exactly once when M <= 64 * TILES; the kernel is then
+// bound by that stream.
+constexpr int kRowsF = 16;
+
+template <int EPI, int TILES, bool HAS_TAU>
+__global__ __launch_bounds__(kWaves * 64) void bgemm_f32_kernel(
+    const float *__restrict__ x, int64_t n, int32_t K, int64_t ldx, const float *__restrict__ tau,
+    int32_t kw32, const uint32_t *__restrict__ w32, int32_t M, int64_t w_stride32,
+    const int32_t *__restrict__ T, const float *__restrict__ alpha, void *__restrict__ out,
+    int64_t out_stride)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRowsF;
+    if (row0 >= n)
+        return;
+    const int ct0 = blockIdx.y * TILES;
+    const uint32_t *wrow[TILES];
+    bool c_ok[TILES];
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+        const int c = (ct0 + t) * 64 + lane;
+        c_ok[t] = c < M;
+        wrow[t] = w32 + (int64_t)(c_ok[t] ? c : 0) * w_stride32;
+    }
+    int acc[kRowsF][TILES];
+#pragma unroll
+    for (int r = 0; r < kRowsF; ++r)
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+            acc[r][t] = 0;
+
+    for (int k0 = 0; k0 < kw32; k0 += kChunk) { // 8 words of 32 bits = 4 votes of 64 floats
+        uint32_t wv[TILES][kChunk];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j)
+                wv[t][j] = (k0 + j < kw32) ? wrow[t][k0 + j] : 0u;
+#pragma unroll
+        for (int b = 0; b < kChunk / 2; ++b) {
+            const int32_t k = k0 * 32 + b * 64 + lane;
+            const bool ok = k < K;
+            const int32_t kc = ok ? k : K - 1; // clamped: the loads below are unconditional,
+            const float tv = HAS_TAU ? tau[kc] : 0.0f; // so all 16 are in flight together
+            float v[kRowsF];
+#pragma unroll
+            for (int r = 0; r < kRowsF; ++r) {
+                const int64_t row = (row0 + r < n) ? row0 + r : n - 1; // wave-uniform
+                v[r] = x[row * ldx + kc];
+            }
+#pragma unroll
+            for (int r = 0; r < kRowsF; ++r) {
+                // beyond K the vote is 0 and so are the weight words: nothing is added
+                const uint64_t m = __ballot(ok && v[r] >= tv);
+                const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+#pragma unroll
+                for (int t = 0; t < TILES; ++t)
+                    acc[r][t] += __popc(lo ^ wv[t][2 * b]) + __popc(hi ^ wv[t][2 * b + 1]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+        const int ct = ct0 + t;
+        const int c = ct * 64 + lane;
+        if (ct * 64 >= M)
+            break; // wave-uniform
+        if (EPI == BITGNN_EPI_THRESH_BITS) {
+            const int32_t tc = c_ok[t] ? T[c] : 0;
+            uint64_t mine = 0;
+#pragma unroll
+            for (int r = 0; r < kRowsF; ++r) {
+                const int32_t z = K - 2 * acc[r][t];
+                const uint64_t m = __ballot(c_ok[t] && z >= tc);
+                if (lane == r)
+                    mine = m;
+            }
+            if (lane < kRowsF && row0 + lane < n)
+                ((uint64_t *)out)[(row0 + lane) * out_stride + ct] = mine;
+        } else if (EPI == BITGNN_EPI_RAW_I32) {
+#pragma unroll
+            for (int r = 0; r < kRowsF; ++r)
+                if (c_ok[t] && row0 + r < n)
+                    ((int32_t *)out)[(row0 + r) * out_stride + c] = K - 2 * acc[r][t];
+        } else {
+            const float a = c_ok[t] ? alpha[c] : 0.0f;
+#pragma unroll
+            for (int r = 0; r < kRowsF; ++r)
+                if (c_ok[t] && row0 + r < n)
+                    ((float *)out)[(row0 + r) * out_stride + c] =
+                        a * (float)(K - 2 * acc[r][t]);
+        }
+    }
+}
+
+template <int EPI, int TILES>
+void launch_bgemm_f32(hipStream_t s, dim3 grid, const float *x, int64_t n, int32_t K, int64_t ldx,
+                      const float *tau, int32_t kw32, const uint32_t *w32, int32_t M,
+                      int64_t w_stride32, const int32_t *T, const float *alpha, void *out,
+                      int64_t out_stride)
+{
+    if (tau)
+        bgemm_f32_kernel<EPI, TILES, true><<<grid, kWaves * 64, 0, s>>>(
+            x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);
+    else
+        bgemm_f32_kernel<EPI, TILES, false><<<grid, kWaves * 64, 0, s>>>(
+            x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);
+}
+
+template <int EPI>
+void launch_bgemm_f32_tiles(hipStream_t s, int64_t n, int32_t M, const float *x, int32_t K,
+                            int64_t ldx, const float *tau, int32_t kw32, const uint32_t *w32,
+                            int64_t w_stride32, const int32_t *T, const float *alpha, void *out,
+                            int64_t out_stride)
+{
+    const int mt = (M + 63) / 64;
+    const unsigned gx = (unsigned)((n + kWaves * kRowsF - 1) / (kWaves * kRowsF));
+    if (mt == 1)
+        launch_bgemm_f32<EPI, 1>(s, dim3(gx, 1), x, n, K, ldx, tau, kw32, w32, M, w_stride32, T,
+                                 alpha, out, out_stride);
+    else if (mt == 2)
+        launch_bgemm_f32<EPI, 2>(s, dim3(gx, 1), x, n, K, ldx, tau, kw32, w32, M, w_stride32, T,
+                                 alpha, out, out_stride);
+    else
+        launch_bgemm_f32<EPI, 4>(s, dim3(gx, (unsigned)((mt + 3) / 4)), x, n, K, ldx, tau, kw32,
+                                 w32, M, w_stride32, T, alpha, out, out_stride);
+}
+
 } // namespace
 
 int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,
@@ -179,4 +316,80 @@ extern "C" int bitgnn_bgemm(bitgnn_ctx *ctx, void *stream, const uint64_t *xbits
     BG_NEED_DEVICE(ctx);
     return bg_launch_bgemm(ctx, (hipStream_t)stream, xbits, n, x_stride, K, kwords, wbits, M,
                            w_stride, epilogue, T, alpha, out, out_stride);
+}
+
+int bg_check_bgemm_f32(bitgnn_ctx *ctx, const float *x, int64_t n, int32_t K, int64_t ldx,
+                       const float *tau, const uint64_t *wbits, int32_t M, int64_t w_stride,
+                       int epilogue, const int32_t *T, const float *alpha, const void *out,
+                       int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, n >= 0 && K >= 1 && M >= 1, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: n=%lld K=%d M=%d", (long long)n, K, M);
+    const int64_t kwords = ((int64_t)K + 63) / 64;
+    BG_REQUIRE(ctx, ldx >= K && w_stride >= kwords, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: ldx=%lld w_stride=%lld", (long long)ldx, (long long)w_stride);
+    BG_REQUIRE(ctx,
+               epilogue == BITGNN_EPI_RAW_I32 || epilogue == BITGNN_EPI_THRESH_BITS ||
+                   epilogue == BITGNN_EPI_SCALE_F32,
+               BITGNN_ERR_INVALID_ARG, "bitgnn_bgemm_f32: epilogue=%d", epilogue);
+    const int64_t need = epilogue == BITGNN_EPI_THRESH_BITS ? (M + 63) / 64 : M;
+    BG_REQUIRE(ctx, out_stride >= need, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: out_stride=%lld < %lld", (long long)out_stride, (long long)need);
+    BG_REQUIRE(ctx, wbits && (n == 0 || (x && out)), BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: null pointer");
+    BG_REQUIRE(ctx, epilogue != BITGNN_EPI_THRESH_BITS || T, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: THRESH_BITS needs T");
+    BG_REQUIRE(ctx, epilogue != BITGNN_EPI_SCALE_F32 || alpha, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_bgemm_f32: SCALE_F32 needs alpha");
+    BG_REQUIRE(ctx,
+               bg_aligned(x, 4) && bg_aligned(tau, 4) && bg_aligned(wbits, 8) && bg_aligned(T, 4) &&
+                   bg_aligned(alpha, 4) &&
+                   bg_aligned(out, epilogue == BITGNN_EPI_THRESH_BITS ? 8 : 4),
+               BITGNN_ERR_ALIGNMENT, "bitgnn_bgemm_f32: misaligned pointer");
+    return BITGNN_OK;
+}
+
+int bg_launch_bgemm_f32(bitgnn_ctx *ctx, hipStream_t s, const float *x, int64_t n, int32_t K,
+                        int64_t ldx, const float *tau, const uint64_t *wbits, int32_t M,
+                        int64_t w_stride, int epilogue, const int32_t *T, const float *alpha,
+                        void *out, int64_t out_stride)
+{
+    if (n == 0)
+        return BITGNN_OK;
+    BG_REQUIRE(ctx, (n + kWaves * kRowsF - 1) / (kWaves * kRowsF) < (1ll << 31),
+               BITGNN_ERR_UNSUPPORTED, "bitgnn_bgemm_f32: n too large");
+    const int32_t kw32 = (int32_t)(((int64_t)K + 63) / 64) * 2;
+    const uint32_t *w32 = (const uint32_t *)wbits;
+    switch (epilogue) {
+    case BITGNN_EPI_THRESH_BITS:
+        launch_bgemm_f32_tiles<BITGNN_EPI_THRESH_BITS>(s, n, M, x, K, ldx, tau, kw32, w32,
+                                                       w_stride * 2, T, alpha, out, out_stride);
+        break;
+    case BITGNN_EPI_RAW_I32:
+        launch_bgemm_f32_tiles<BITGNN_EPI_RAW_I32>(s, n, M, x, K, ldx, tau, kw32, w32,
+                                                   w_stride * 2, T, alpha, out, out_stride);
+        break;
+    default:
+        launch_bgemm_f32_tiles<BITGNN_EPI_SCALE_F32>(s, n, M, x, K, ldx, tau, kw32, w32,
+                                                     w_stride * 2, T, alpha, out, out_stride);
+        break;
+    }
+    BG_LAUNCH_CHECK(ctx, "bitgnn_bgemm_f32");
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_bgemm_f32(bitgnn_ctx *ctx, void *stream, const float *x, int64_t n, int32_t K,
+                                int64_t ldx, const float *tau, const uint64_t *wbits, int32_t M,
+                                int64_t w_stride, int epilogue, const int32_t *T,
+                                const float *alpha, void *out, int64_t out_stride)
+{
+    int rc = bg_check_bgemm_f32(ctx, x, n, K, ldx, tau, wbits, M, w_stride, epilogue, T, alpha,
+                                out, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    return bg_launch_bgemm_f32(ctx, (hipStream_t)stream, x, n, K, ldx, tau, wbits, M, w_stride,
+                               epilogue, T, alpha, out, out_stride);
 }

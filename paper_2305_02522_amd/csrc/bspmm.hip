@@ -127,13 +127,19 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
     const uint32_t *hw = h32 + w;
     uint32_t blk = 0; // blocks of 16 neighbours consumed so far (wave-uniform)
     while (__ballot(e < end) != 0ull) {
+        // clamped, unconditional loads (masked afterwards): the 16 index loads and then
+        // the 16 gathers are in flight together instead of one at a time
         uint32_t x[kGroup];
+        int32_t j[kGroup];
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-            const bool ok = e + u < end;
-            const int32_t j = ok ? col[e + u] : 0;
-            x[u] = ok ? hw[(int64_t)j * h_stride32] : 0u;
-        }
+        for (int u = 0; u < kGroup; ++u)
+            j[u] = col[e + u < end ? e + u : (deg ? end - 1 : 0u)];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) // lanes past their row end gather node 0 (always valid)
+            x[u] = hw[(int64_t)(e + u < end ? j[u] : 0) * h_stride32];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u)
+            x[u] = e + u < end ? x[u] : 0u;
         e = (end - e > (uint32_t)kGroup) ? e + kGroup : end;
 
         // 16 words -> planes 0..3 plus one carry of weight 16

@@ -128,6 +128,15 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
                                   const uint64_t *wbits, int32_t M, int64_t w_stride,
                                   const float *alpha, float *logits, int64_t ldo);
 
+int bg_check_bgemm_f32(bitgnn_ctx *ctx, const float *x, int64_t n, int32_t K, int64_t ldx,
+                       const float *tau, const uint64_t *wbits, int32_t M, int64_t w_stride,
+                       int epilogue, const int32_t *T, const float *alpha, const void *out,
+                       int64_t out_stride);
+int bg_launch_bgemm_f32(bitgnn_ctx *ctx, hipStream_t s, const float *x, int64_t n, int32_t K,
+                        int64_t ldx, const float *tau, const uint64_t *wbits, int32_t M,
+                        int64_t w_stride, int epilogue, const int32_t *T, const float *alpha,
+                        void *out, int64_t out_stride);
+
 // Argument validation of the public calls, shared with the layer drivers.
 int bg_check_bgemm(bitgnn_ctx *ctx, const uint64_t *xbits, int64_t n, int64_t x_stride, int32_t K,
                    int32_t kwords, const uint64_t *wbits, int32_t M, int64_t w_stride,

@@ -33,6 +33,35 @@ extern "C" int bitgnn_gcn_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj 
                            out_stride);
 }
 
+extern "C" int bitgnn_gcn_layer_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                    const float *x, int32_t K, int64_t ldx, const float *tau,
+                                    const uint64_t *wbits, int32_t M, int64_t w_stride,
+                                    const int32_t *T_mm, const int32_t *T_agg, uint64_t *tmp_bits,
+                                    uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_layer_f32: adj is null");
+    const int64_t n = adj->n;
+    const int64_t mw = ((int64_t)M + 63) / 64;
+    int rc = bg_check_bgemm_f32(ctx, x, n, K, ldx, tau, wbits, M, w_stride, BITGNN_EPI_THRESH_BITS,
+                                T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_bspmm(ctx, adj, tmp_bits, M, mw, BITGNN_EPI_THRESH_BITS, T_agg, out_bits,
+                        out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm_f32(ctx, s, x, n, K, ldx, tau, wbits, M, w_stride, BITGNN_EPI_THRESH_BITS,
+                             T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_bspmm(ctx, s, adj, tmp_bits, M, mw, BITGNN_EPI_THRESH_BITS, T_agg, out_bits,
+                           out_stride);
+}
+
 extern "C" int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                                     const uint64_t *xbits, int64_t x_stride, int32_t K,
                                     int32_t kwords, const uint64_t *wbits, int32_t M,

@@ -12,7 +12,7 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 8;
+constexpr int kUnroll = 16;
 
 template <typename T> __device__ __forceinline__ bool bin_pred(T v, float tau);
 template <> __device__ __forceinline__ bool bin_pred<float>(float v, float tau) { return v >= tau; }
@@ -43,8 +43,11 @@ __global__ __launch_bounds__(kBlock) void pack_rows_kernel(const T *__restrict__
         for (int u = 0; u < kUnroll; ++u) {
             const int32_t k = w * 64 + lane;
             ok[u] = (q0 + t0 + u < total) && (k < K);
-            v[u] = ok[u] ? x[row * ldx + k] : (T)0;
-            tv[u] = (HAS_TAU && ok[u]) ? tau[k] : 0.0f;
+            // clamped, unconditional loads: all kUnroll of them are in flight together
+            const int32_t kc = k < K ? k : K - 1;
+            const int64_t rc = row < n ? row : n - 1;
+            v[u] = x[rc * ldx + kc];
+            tv[u] = HAS_TAU ? tau[kc] : 0.0f;
             if (++w == words) {
                 w = 0;
                 ++row;

@@ -200,6 +200,42 @@ def test_bgemm_three_epilogues(B, ctx, n, K, M):
     assert rel_close(of.cpu().numpy(), orc.scale(z, alpha))
 
 
+@pytest.mark.parametrize("n,K,M", [(1, 1, 1), (70, 63, 7), (300, 65, 65), (1000, 602, 128),
+                                   (500, 1433, 64), (129, 512, 256), (257, 100, 300),
+                                   (4099, 130, 41)])
+def test_bgemm_f32_binarizes_inside(B, ctx, n, K, M):
+    r = np.random.default_rng(K * 31 + M)
+    ldx = K + (3 if K % 2 else 0)
+    x = r.standard_normal((n, ldx)).astype(np.float32)
+    x[r.random((n, ldx)) < 0.05] = 0.0
+    x[r.random((n, ldx)) < 0.02] = -0.0
+    w = W.pm1(r, (K, M))
+    kw = (K + 63) // 64
+    wb = _pack_host(np.ascontiguousarray(w.T))
+    for tau in (None, r.standard_normal(K).astype(np.float32)):
+        if tau is not None:
+            x[0, :K] = tau
+        v = orc.bin_f32(x[:, :K], tau)
+        z = orc.bmm(v, w)
+        out = torch.full((n, M + 1), 5, dtype=torch.int32, device="cuda")
+        B.bgemm_f32(ctx, dev(x), n, K, ldx, None if tau is None else dev(tau), wb, M, kw,
+                    B.EPI_RAW_I32, None, None, out, M + 1)
+        t = r.integers(-6, 7, size=M).astype(np.int32)
+        mw = (M + 63) // 64
+        ob = torch.full((n, mw), -1, dtype=torch.int64, device="cuda")
+        B.bgemm_f32(ctx, dev(x), n, K, ldx, None if tau is None else dev(tau), wb, M, kw,
+                    B.EPI_THRESH_BITS, dev(t), None, ob, mw)
+        alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
+        of = torch.zeros((n, M), dtype=torch.float32, device="cuda")
+        B.bgemm_f32(ctx, dev(x), n, K, ldx, None if tau is None else dev(tau), wb, M, kw,
+                    B.EPI_SCALE_F32, None, dev(alpha), of, M)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :M], z) and np.all(got[:, M] == 5)
+        assert np.array_equal(words_np(ob), orc.to_words(orc.rebin(z, t)))
+        assert rel_close(of.cpu().numpy(), orc.scale(z, alpha))
+
+
 def test_bgemm_segmented_k_with_interior_pad_bits(B, ctx):
     # [self | nbr] rows: two 100-bit segments, each padded to 128 bits, K = 200
     r = np.random.default_rng(99)
