@@ -88,6 +88,15 @@ const char *bitgnn_last_error(const bitgnn_ctx *ctx);
 int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
                           int32_t min_avg_degree);
 
+/* Optional timing of the main aggregation kernel of every bit-SpMM call (the
+ * LDS-staged kernel, or the CSR kernel on sparse graphs; the small permute / merge
+ * kernels around it are not included).  While enabled, each launch is bracketed by
+ * HIP events on the call's stream; up to 256 launches are kept.
+ * bitgnn_ctx_kernel_times waits for the recorded launches, writes their durations
+ * in milliseconds (launch order) to ms[0..*count) and empties the list. */
+int bitgnn_ctx_kernel_timing(bitgnn_ctx *ctx, int enable);
+int bitgnn_ctx_kernel_times(bitgnn_ctx *ctx, float *ms, int32_t capacity, int32_t *count);
+
 /* ---- BIN: binarize and pack (Section 2.2 sign rule; Section 2.3) --------- */
 
 /* out[i][k/64] bit k%64 = (x[i*ldx + k] >= tau[k]) for k < K; tau == NULL means

@@ -45,6 +45,9 @@ _SIGNATURES = {
     "bitgnn_ctx_destroy": (None, [_vp]),
     "bitgnn_last_error": (ctypes.c_char_p, [_vp]),
     "bitgnn_ctx_set_tuning": (_int, [_vp, _i32, _i32, _i32]),
+    "bitgnn_ctx_kernel_timing": (_int, [_vp, _int]),
+    "bitgnn_ctx_kernel_times": (_int, [_vp, ctypes.POINTER(ctypes.c_float), _i32,
+                                       ctypes.POINTER(_i32)]),
     "bitgnn_pack_f32": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _vp, _i64]),
     "bitgnn_pack_i8": (_int, [_vp, _vp, _vp, _i64, _i32, _i64, _vp, _i64]),
     "bitgnn_pack_weights_i8": (_int, [_vp, _vp, _vp, _i32, _i32, _i64, _vp, _i64]),
@@ -170,6 +173,17 @@ def words(k: int) -> int:
 
 def ctx_set_tuning(ctx: Context, cb_nodes: int, part_len: int, min_avg_degree: int):
     ctx.check(_lib.bitgnn_ctx_set_tuning(ctx.handle, cb_nodes, part_len, min_avg_degree))
+
+
+def ctx_kernel_timing(ctx: Context, enable: bool):
+    ctx.check(_lib.bitgnn_ctx_kernel_timing(ctx.handle, 1 if enable else 0))
+
+
+def ctx_kernel_times(ctx: Context) -> List[float]:
+    buf = (ctypes.c_float * 256)()
+    cnt = _i32()
+    ctx.check(_lib.bitgnn_ctx_kernel_times(ctx.handle, buf, 256, ctypes.byref(cnt)))
+    return [buf[i] for i in range(cnt.value)]
 
 
 def pack_f32(ctx: Context, x, n, K, ldx, tau, out, out_stride):

@@ -673,9 +673,11 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     for (int win = 0; win * 4 < W32; ++win) {
         blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
             h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm);
+        bg_time_begin(ctx, s);
         bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
             b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+        bg_time_end(ctx, s);
         BG_LAUNCH_CHECK(ctx, "bspmm_blk");
         switch (P) {
         case 12:
@@ -720,9 +722,11 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
         (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm);
+    bg_time_begin(ctx, s);
     bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
         hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
         b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+    bg_time_end(ctx, s);
     BG_LAUNCH_CHECK(ctx, "bspmm_blk");
     const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
     const uint32_t *w32 = (const uint32_t *)wbits;
@@ -762,6 +766,7 @@ int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const
     const int64_t grid = (threads + kBlock - 1) / kBlock;
     BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm: N*C too large");
     const uint32_t *h32 = (const uint32_t *)hbits;
+    bg_time_begin(ctx, s);
     switch (P) {
     case 12:
         launch_bspmm_p<12>(s, (unsigned)grid, epilogue, adj, h32, h_stride * 2, C, W32, seeds, out,
@@ -780,6 +785,7 @@ int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const
                            out_stride);
         break;
     }
+    bg_time_end(ctx, s);
     BG_LAUNCH_CHECK(ctx, "bitgnn_bspmm");
     return BITGNN_OK;
 }

@@ -24,7 +24,26 @@ struct bitgnn_ctx {
     // per-part partial counters)
     void *ws;
     size_t ws_bytes;
+    // optional HIP-event timing of the main aggregation kernel (bitgnn_ctx_kernel_timing)
+    int timing;
+    int n_timed;
+    hipEvent_t tev[2 * 256];
 };
+
+static const int kMaxTimed = 256;
+// Brackets one kernel launch with events when timing is on (no-ops otherwise).
+static inline void bg_time_begin(bitgnn_ctx *ctx, hipStream_t s)
+{
+    if (ctx->timing && ctx->n_timed < kMaxTimed)
+        (void)hipEventRecord(ctx->tev[2 * ctx->n_timed], s);
+}
+static inline void bg_time_end(bitgnn_ctx *ctx, hipStream_t s)
+{
+    if (ctx->timing && ctx->n_timed < kMaxTimed) {
+        (void)hipEventRecord(ctx->tev[2 * ctx->n_timed + 1], s);
+        ++ctx->n_timed;
+    }
+}
 
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {

@@ -45,6 +45,9 @@ extern "C" void bitgnn_ctx_destroy(bitgnn_ctx *ctx)
         (void)hipFree(ctx->seed_table);
     if (ctx->ws)
         (void)hipFree(ctx->ws);
+    for (int i = 0; i < 2 * kMaxTimed; ++i)
+        if (ctx->tev[i])
+            (void)hipEventDestroy(ctx->tev[i]);
     free(ctx);
 }
 
@@ -81,5 +84,36 @@ int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes)
     bytes = (bytes + (1u << 20)) & ~(size_t)((1u << 20) - 1);
     BG_HIP(ctx, hipMalloc(&ctx->ws, bytes));
     ctx->ws_bytes = bytes;
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_ctx_kernel_timing(bitgnn_ctx *ctx, int enable)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_NEED_DEVICE(ctx);
+    if (enable && !ctx->tev[0])
+        for (int i = 0; i < 2 * kMaxTimed; ++i)
+            BG_HIP(ctx, hipEventCreate(&ctx->tev[i]));
+    ctx->timing = enable ? 1 : 0;
+    ctx->n_timed = 0;
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_ctx_kernel_times(bitgnn_ctx *ctx, float *ms, int32_t capacity,
+                                       int32_t *count)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, ms && count && capacity >= 0, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_ctx_kernel_times: null pointer or negative capacity");
+    BG_NEED_DEVICE(ctx);
+    int k = 0;
+    for (; k < ctx->n_timed && k < capacity; ++k) {
+        BG_HIP(ctx, hipEventSynchronize(ctx->tev[2 * k + 1]));
+        BG_HIP(ctx, hipEventElapsedTime(&ms[k], ctx->tev[2 * k], ctx->tev[2 * k + 1]));
+    }
+    *count = k;
+    ctx->n_timed = 0;
     return BITGNN_OK;
 }
