@@ -20,8 +20,11 @@
 //  - parts are ordered by (first block, last block, length); 64 consecutive
 //    parts form a slice (one wavefront, one part per lane), 16 slices a
 //    workgroup.  For every (slice, block) tile the ids are stored lane-
-//    interleaved in groups of 4 steps: group g holds idx16[(g*64+lane)*4+k],
-//    padded with the id `cbn`, which addresses an all-zero LDS row.
+//    interleaved in groups of kGroupSteps steps: group g holds
+//    idx16[(g*64+lane)*kGroupSteps+k], padded with the id `cbn`, which addresses
+//    an all-zero LDS row.  The groups of a slice are consecutive, so a wavefront
+//    reads one contiguous stream; one padding group closes the array so that
+//    reading one group ahead is always in bounds.
 #include "prims.h"
 
 #include <stdlib.h>
@@ -165,18 +168,27 @@ __global__ __launch_bounds__(64) void tile_kernel(
         if (!FILL) {
             const uint32_t m = wave_max_u32(cnt);
             if (lane == 0)
-                tile_group[t0 + cb - lo] = (m + 3) / 4;
+                tile_group[t0 + cb - lo] = (m + kGroupSteps - 1) / kGroupSteps;
         } else {
             const uint32_t g0 = tile_group[t0 + cb - lo];
-            const uint32_t steps = (tile_group[t0 + cb - lo + 1] - g0) * 4;
+            const uint32_t steps = (tile_group[t0 + cb - lo + 1] - g0) * kGroupSteps;
             for (uint32_t k = 0; k < steps; ++k) {
                 const uint32_t id =
                     k < cnt ? (uint32_t)((skeys[first + k] & mask) - (uint64_t)cb * (uint32_t)cbn)
                             : (uint32_t)cbn;
-                idx16[((uint64_t)(g0 + k / 4) * 64 + lane) * 4 + (k & 3)] = (uint16_t)id;
+                idx16[((uint64_t)(g0 + k / kGroupSteps) * 64 + lane) * kGroupSteps +
+                      (k % kGroupSteps)] = (uint16_t)id;
             }
         }
     }
+}
+
+// the padding group behind the last tile
+__global__ void tail_group_kernel(uint16_t *__restrict__ idx16, uint32_t G, int cbn)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 64u * kGroupSteps)
+        idx16[(uint64_t)G * 64 * kGroupSteps + i] = (uint16_t)cbn;
 }
 
 __global__ void part_pos_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
@@ -214,7 +226,7 @@ __global__ void wg_cost_kernel(const uint32_t *__restrict__ wg_cb,
     const uint32_t s0 = w * 16, s1 = min(s0 + 16, S);
     const uint64_t groups = tile_group[sl_tile_base[s1]] - tile_group[sl_tile_base[s0]];
     const uint64_t fills = (wg_cb[w] >> 16) - (wg_cb[w] & 0xFFFFu) + 1;
-    const uint64_t cost = groups * 73 + fills * 2500;
+    const uint64_t cost = groups * (73 * kGroupSteps / 4) + fills * 2500;
     keys[w] = ((0xFFFFFFFFull - min(cost, (uint64_t)0xFFFFFFFFull)) << 32) | w;
 }
 
@@ -329,11 +341,14 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     uint32_t G = 0;
     BG_HIP(ctx, hipMemcpyAsync(&G, tile_group.as<uint32_t>() + T, 4, hipMemcpyDeviceToHost, s));
     BG_HIP(ctx, hipStreamSynchronize(s));
-    if ((uint64_t)G * 256 >= (1ull << 32))
+    constexpr uint64_t kGroupIds = 64ull * kGroupSteps;
+    if (((uint64_t)G + 1) * kGroupIds * 2 >= (1ull << 32)) // the kernel uses 32-bit byte offsets
         return BITGNN_OK;
 
     DevBuf idx16;
-    BG_HIP(ctx, idx16.alloc((size_t)G * 256 * 2));
+    BG_HIP(ctx, idx16.alloc(((size_t)G + 1) * kGroupIds * 2));
+    tail_group_kernel<<<blocks_for((int64_t)kGroupIds, 256), 256, 0, s>>>(idx16.as<uint16_t>(), G,
+                                                                         cbn);
     tile_kernel<true><<<S, 64, 0, s>>>(svkeys, V, v_beg.as<uint32_t>(), v_end.as<uint32_t>(), skeys,
                                        cbits, cbn, sl_cb.as<uint32_t>(),
                                        sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
@@ -365,7 +380,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     b->n_wgs = W;
     b->n_tiles = T;
     b->n_groups = G;
-    b->device_bytes = (size_t)G * 512 + ((size_t)T + 1) * 4 + ((size_t)S * 2 + 1) * 4 +
+    b->device_bytes = ((size_t)G + 1) * kGroupIds * 2 + ((size_t)T + 1) * 4 + ((size_t)S * 2 + 1) * 4 +
                       (size_t)W * 4 + ((size_t)n + 1) * 4 + (size_t)V * 4;
     b->wg_order = (uint32_t *)wg_order.release();
     b->wg_cb = (uint32_t *)wg_cb.release();

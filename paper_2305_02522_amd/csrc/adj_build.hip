@@ -303,7 +303,7 @@ extern "C" int bitgnn_adj_blocked_info(const bitgnn_adj *adj, int64_t *parts, in
     if (tiles)
         *tiles = b ? b->n_tiles : 0;
     if (stored_ids)
-        *stored_ids = b ? (int64_t)b->n_groups * 256 : 0;
+        *stored_ids = b ? (int64_t)b->n_groups * 64 * kGroupSteps : 0;
     if (cb_nodes)
         *cb_nodes = b ? b->cbn : 0;
     return BITGNN_OK;

@@ -249,18 +249,19 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
 constexpr int kPartPlanes = 10;
 constexpr int kBlkThreads = 1024;
 
-constexpr int kPendTop = 6; // levels 2..5 park a carry; above, carries ripple (rare)
+constexpr int kPendLow = 3; // a block of 8 gathers produces one carry of weight 2^3
+constexpr int kPendTop = 6; // levels 3..5 park a carry; above, carries ripple (rare)
 
 // Adds a carry of weight 2^P0 into the counters.  Level p holds a parked carry iff
-// bit (p-2) of blk (the number of groups consumed so far): a binary counter, so
-// the control flow is wave-uniform and every register index is static.
+// bit (p - kPendLow) of blk (the number of 8-step blocks consumed so far): a binary
+// counter, so the control flow is wave-uniform and every register index is static.
 template <int P0>
 __device__ __forceinline__ void blk_cascade(uint32_t (&acc)[kPartPlanes][4],
                                             uint32_t (&pend)[kPartPlanes][4],
                                             uint32_t (&carry)[4], uint32_t blk)
 {
     if constexpr (P0 < kPendTop) {
-        if (!((blk >> (P0 - 2)) & 1u)) {
+        if (!((blk >> (P0 - kPendLow)) & 1u)) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 pend[P0][q] = carry[q];
@@ -274,7 +275,7 @@ __device__ __forceinline__ void blk_cascade(uint32_t (&acc)[kPartPlanes][4],
             blk_cascade<P0 + 1>(acc, pend, carry, blk);
         }
     } else {
-        // ripple the carry through the upper planes (once per 2^(kPendTop-2) groups)
+        // ripple the carry through the upper planes (once per 2^(kPendTop-kPendLow) blocks)
 #pragma unroll
         for (int p = kPendTop; p < kPartPlanes; ++p)
 #pragma unroll
@@ -302,28 +303,34 @@ __global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_s
     hperm[slot] = v;
 }
 
-// One group: 4 gathers of 16-byte rows from LDS, added into the bit-sliced counters.
-__device__ __forceinline__ void blk_consume(uint32_t i0, uint32_t i1, uint32_t i2, uint32_t i3,
-                                            const uint4 *hblk, uint32_t (&acc)[kPartPlanes][4],
+// One block of 8 steps: gathers of 16-byte rows from LDS, added into the bit-sliced
+// counters through a carry-save tree (7 adders per 8 inputs and 32-channel word).
+__device__ __forceinline__ void blk_consume(const uint32_t (&id)[8], const uint4 *hblk,
+                                            uint32_t (&acc)[kPartPlanes][4],
                                             uint32_t (&pend)[kPartPlanes][4], uint32_t blk)
 {
-    const uint4 v0 = hblk[i0];
-    const uint4 v1 = hblk[i1];
-    const uint4 v2 = hblk[i2];
-    const uint4 v3 = hblk[i3];
-    const uint32_t x0[4] = {v0.x, v0.y, v0.z, v0.w};
-    const uint32_t x1[4] = {v1.x, v1.y, v1.z, v1.w};
-    const uint32_t x2[4] = {v2.x, v2.y, v2.z, v2.w};
-    const uint32_t x3[4] = {v3.x, v3.y, v3.z, v3.w};
+    uint32_t x[8][4];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint4 v = hblk[id[k]];
+        x[k][0] = v.x;
+        x[k][1] = v.y;
+        x[k][2] = v.z;
+        x[k][3] = v.w;
+    }
     uint32_t carry[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        uint32_t a2, b2;
-        csa(acc[0][q], x0[q], x1[q], a2);
-        csa(acc[0][q], x2[q], x3[q], b2);
-        csa(acc[1][q], a2, b2, carry[q]); // weight 4
+        uint32_t t0, t1, t2, t3, f0, f1;
+        csa(acc[0][q], x[0][q], x[1][q], t0);
+        csa(acc[0][q], x[2][q], x[3][q], t1);
+        csa(acc[0][q], x[4][q], x[5][q], t2);
+        csa(acc[0][q], x[6][q], x[7][q], t3);
+        csa(acc[1][q], t0, t1, f0);
+        csa(acc[1][q], t2, t3, f1);
+        csa(acc[2][q], f0, f1, carry[q]); // weight 8
     }
-    blk_cascade<2>(acc, pend, carry, blk);
+    blk_cascade<kPendLow>(acc, pend, carry, blk);
 }
 
 #ifdef BITGNN_PROFILE
@@ -331,10 +338,33 @@ __device__ unsigned long long *g_blk_prof = nullptr; // per workgroup: start, en
 #define BLK_PROF_T() ((tid == 0) ? clock64() : 0)
 #endif
 
+// The 16-bit ids of one lane for one group: kGroupSteps / 2 dwords, one vector load each.
+struct blk_ids {
+    uint32_t w[kGroupSteps / 2];
+};
+// The id array is smaller than 4 GiB (checked when the format is built), so a group
+// is addressed as uniform base + 32-bit byte offset.
+__device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx, uint32_t g,
+                                                int lane)
+{
+    const uint32_t byte = (g * 64u + (uint32_t)lane) * (uint32_t)(kGroupSteps * 2);
+    const uint4 *p = (const uint4 *)((const char *)idx + byte);
+    blk_ids r;
+#pragma unroll
+    for (int j = 0; j < kGroupSteps / 8; ++j) {
+        const uint4 v = p[j];
+        r.w[4 * j + 0] = v.x;
+        r.w[4 * j + 1] = v.y;
+        r.w[4 * j + 2] = v.z;
+        r.w[4 * j + 3] = v.w;
+    }
+    return r;
+}
+
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_order,
     const uint32_t *__restrict__ wg_cb, const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
-    const uint32_t *__restrict__ tile_group, const uint2 *__restrict__ idx, uint32_t S,
+    const uint32_t *__restrict__ tile_group, const uint32_t *__restrict__ idx, uint32_t S,
     uint32_t V, uint4 *__restrict__ partial)
 {
     extern __shared__ uint4 hblk[]; // cbn rows + one all-zero row
@@ -349,13 +379,18 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const bool has = slice < S;
     const uint32_t wcb = wg_cb[wg];
     const uint32_t wlo = wcb & 0xFFFFu, whi = wcb >> 16;
-    uint32_t mylo = 1, myhi = 0, t0 = 0;
+    uint32_t mylo = 1, myhi = 0, t0 = 0, g = 0;
     if (has) {
         const uint32_t c = sl_cb[slice];
         mylo = c & 0xFFFFu;
         myhi = c >> 16;
         t0 = sl_tile_base[slice];
+        g = tile_group[t0];
     }
+    // The groups of a slice are one contiguous stream: group g + 1 is requested
+    // while group g is consumed, across tile boundaries and LDS refills alike.
+    // Reading one group past the stream's end is in bounds (padding group).
+    blk_ids nxt = blk_load_ids(idx, g, lane);
     if (tid == 0)
         hblk[cbn] = make_uint4(0u, 0u, 0u, 0u);
 
@@ -367,7 +402,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             acc[p][q] = 0u;
             pend[p][q] = 0u;
         }
-    uint32_t blk = 0; // groups of 4 steps consumed by this wavefront
+    uint32_t blk = 0; // blocks of 8 steps consumed by this wavefront
 #ifdef BITGNN_PROFILE
     const long long p_start = BLK_PROF_T();
     const unsigned long long p_wall0 = (tid == 0) ? wall_clock64() : 0;
@@ -406,19 +441,26 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
         { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
 #endif
         if (cb >= mylo && cb <= myhi) { // wave-uniform
-            const uint32_t tile = t0 + cb - mylo;
-            uint32_t g = tile_group[tile];
-            const uint32_t g1 = tile_group[tile + 1];
-            uint2 nxt = make_uint2(0u, 0u);
-            if (g < g1)
-                nxt = idx[(uint64_t)g * 64 + lane];
+            const uint32_t g1 = tile_group[t0 + cb - mylo + 1];
             for (; g < g1; ++g) {
-                const uint2 pk = nxt;
-                if (g + 1 < g1)
-                    nxt = idx[(uint64_t)(g + 1) * 64 + lane];
-                blk_consume(pk.x & 0xFFFFu, pk.x >> 16, pk.y & 0xFFFFu, pk.y >> 16, hblk, acc, pend,
-                            blk);
-                ++blk;
+                // Unpack the ids first and pin them in registers: after that
+                // `nxt` is dead, the next request reuses its registers without a copy, and
+                // the wait for it moves to the top of the next iteration.
+                uint32_t id[kGroupSteps / 8][8];
+#pragma unroll
+                for (int j = 0; j < kGroupSteps / 2; ++j) {
+                    id[j / 4][2 * (j % 4)] = nxt.w[j] & 0xFFFFu;
+                    id[j / 4][2 * (j % 4) + 1] = nxt.w[j] >> 16;
+                }
+#pragma unroll
+                for (int j = 0; j < kGroupSteps; ++j)
+                    asm volatile("" : "+v"(id[j / 8][j % 8]) : : "memory");
+                nxt = blk_load_ids(idx, g + 1, lane);
+#pragma unroll
+                for (int j = 0; j < kGroupSteps / 8; ++j) {
+                    blk_consume(id[j], hblk, acc, pend, blk);
+                    ++blk;
+                }
             }
         }
     }
@@ -439,8 +481,9 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     for (int q = 0; q < 4; ++q) {
         uint32_t carry = 0;
 #pragma unroll
-        for (int p = 2; p < kPartPlanes; ++p) {
-            const uint32_t pd = (p < kPendTop && ((blk >> (p - 2)) & 1u)) ? pend[p][q] : 0u;
+        for (int p = kPendLow; p < kPartPlanes; ++p) {
+            const uint32_t pd =
+                (p < kPendTop && ((blk >> (p - kPendLow)) & 1u)) ? pend[p][q] : 0u;
             uint32_t nc;
             csa(acc[p][q], pd, carry, nc);
             carry = nc;
@@ -676,7 +719,7 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
         bg_time_begin(ctx, s);
         bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
-            b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+            b->tile_group, (const uint32_t *)b->idx16, b->n_slices, b->n_vrows, partial);
         bg_time_end(ctx, s);
         BG_LAUNCH_CHECK(ctx, "bspmm_blk");
         switch (P) {
@@ -725,7 +768,7 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     bg_time_begin(ctx, s);
     bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
         hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
-        b->tile_group, (const uint2 *)b->idx16, b->n_slices, b->n_vrows, partial);
+        b->tile_group, (const uint32_t *)b->idx16, b->n_slices, b->n_vrows, partial);
     bg_time_end(ctx, s);
     BG_LAUNCH_CHECK(ctx, "bspmm_blk");
     const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);

@@ -45,6 +45,14 @@ static inline void bg_time_end(bitgnn_ctx *ctx, hipStream_t s)
     }
 }
 
+// Gather steps per group of the blocked format: one lane's ids of a group are
+// kGroupSteps consecutive 16-bit words (one or two 16-byte loads).
+#ifndef BITGNN_GROUP_STEPS
+#define BITGNN_GROUP_STEPS 8
+#endif
+static const int kGroupSteps = BITGNN_GROUP_STEPS;
+static_assert(kGroupSteps == 8 || kGroupSteps == 16, "groups of 8 or 16 steps");
+
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
@@ -53,13 +61,14 @@ struct bitgnn_blocked {
     uint32_t n_slices;      // ceil(V / 64)
     uint32_t n_wgs;         // ceil(slices / 16)
     uint32_t n_tiles;       // (slice, column block) tiles
-    uint32_t n_groups;      // groups of 4 gather steps over all tiles
+    uint32_t n_groups;      // groups of kGroupSteps gather steps over all tiles
     uint32_t *wg_order;     // [n_wgs] workgroups by decreasing estimated work
     uint32_t *wg_cb;        // [n_wgs] first column block | last << 16
     uint32_t *sl_cb;        // [n_slices] first | last << 16
     uint32_t *sl_tile_base; // [n_slices + 1]
-    uint32_t *tile_group;   // [n_tiles + 1] prefix of 4-step groups
-    uint16_t *idx16;        // [n_groups * 256] column ids inside the block; cbn = "none"
+    uint32_t *tile_group;   // [n_tiles + 1] prefix of group counts
+    uint16_t *idx16;        // [(n_groups + 1) * 64 * kGroupSteps] column ids inside the block;
+                            // cbn = "none"; the last group is padding that a prefetch may read
     uint32_t *row_vptr;     // [n + 1] by degree-order slot: first part of the row
     uint32_t *part_pos;     // [V] position of a part in the processing order
     size_t device_bytes;
