@@ -206,7 +206,7 @@ __global__ void wg_range_kernel(const uint32_t *__restrict__ sl_cb, uint32_t S, 
     if (w >= W)
         return;
     uint32_t lo = 0xFFFFu, hi = 0;
-    for (uint32_t s = w * 16; s < w * 16 + 16 && s < S; ++s) {
+    for (uint32_t s = w * kSlicesPerWg; s < (w + 1) * kSlicesPerWg && s < S; ++s) {
         lo = min(lo, sl_cb[s] & 0xFFFFu);
         hi = max(hi, sl_cb[s] >> 16);
     }
@@ -223,7 +223,7 @@ __global__ void wg_cost_kernel(const uint32_t *__restrict__ wg_cb,
     const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W)
         return;
-    const uint32_t s0 = w * 16, s1 = min(s0 + 16, S);
+    const uint32_t s0 = w * kSlicesPerWg, s1 = min(s0 + kSlicesPerWg, S);
     const uint64_t groups = tile_group[sl_tile_base[s1]] - tile_group[sl_tile_base[s0]];
     const uint64_t fills = (wg_cb[w] >> 16) - (wg_cb[w] & 0xFFFFu) + 1;
     const uint64_t cost = groups * (73 * kGroupSteps / 4) + fills * 2500;
@@ -261,7 +261,8 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     const uint32_t n = (uint32_t)adj->n, nnz = (uint32_t)adj->nnz;
     const int cbn = ctx->cb_nodes, part_len = ctx->part_len;
     const int64_t ncb = (adj->n + cbn - 1) / cbn;
-    if (ncb > 4095 || nnz == 0)
+    // (the kernel's workgroup copies at most 8 rows of a block per thread)
+    if (ncb > 4095 || nnz == 0 || cbn > 8 * 64 * kSlicesPerWg)
         return BITGNN_OK; // stays on the CSR path
     int cbits = 1;
     while ((1ll << cbits) < adj->n)
@@ -316,7 +317,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     uint64_t *svkeys = radix_sort(vk_a.as<uint64_t>(), vk_b.as<uint64_t>(), V, 64,
                                   hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
 
-    const uint32_t S = (V + 63) / 64, W = (S + 15) / 16;
+    const uint32_t S = (V + 63) / 64, W = (S + kSlicesPerWg - 1) / kSlicesPerWg;
     DevBuf sl_cb, sl_tile_base, wg_cb, part_pos;
     BG_HIP(ctx, sl_cb.alloc((size_t)S * 4));
     BG_HIP(ctx, sl_tile_base.alloc(((size_t)S + 1) * 4));

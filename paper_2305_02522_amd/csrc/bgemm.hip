@@ -106,16 +106,84 @@ __global__ __launch_bounds__(kWaves * 64) void bgemm_kernel(
 // where the XOR with the lane's weight words wants it.  The packed activations are
 // never written to memory.  A wavefront owns TILES x 64 output channels, so the float
 // matrix is streamed from HBM exactly once when M <= 64 * TILES; the kernel is then
-// bound by that stream.
+// bound by that stream.  To keep the stream sequential for the memory system, a
+// wavefront holds the weight words of a whole K chunk in registers and walks its 16
+// rows one after the other: its requests cover one contiguous span of the matrix
+// (16 rows back to back when ldx == K), two rows in flight at a time.
 constexpr int kRowsF = 16;
 
-template <int EPI, int TILES, bool HAS_TAU>
+template <int TILES>
+struct f32_chunk {
+    // 32-bit weight words per K chunk held in registers (two per vote of 64 floats)
+    static constexpr int words = TILES <= 2 ? 20 : 8;
+};
+
+template <int VOTES, bool HAS_TAU>
+__device__ __forceinline__ void f32_load_row(const float *__restrict__ xrow,
+                                             const int32_t (&kc)[VOTES], float (&v)[VOTES])
+{
+#pragma unroll
+    for (int b = 0; b < VOTES; ++b)
+        v[b] = xrow[kc[b]];
+}
+
+template <int VOTES, int TILES, bool HAS_TAU>
+__device__ __forceinline__ void f32_consume_row(const float (&v)[VOTES], const float (&tv)[VOTES],
+                                                const uint64_t (&okmask)[VOTES],
+                                                const uint32_t (&wv)[TILES][2 * VOTES],
+                                                int (&acc)[TILES])
+{
+#pragma unroll
+    for (int b = 0; b < VOTES; ++b) {
+        // beyond K the vote is 0 and so are the weight words: nothing is added
+        const uint64_t m = __ballot(v[b] >= (HAS_TAU ? tv[b] : 0.0f)) & okmask[b];
+        const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+            acc[t] += __popc(lo ^ wv[t][2 * b]) + __popc(hi ^ wv[t][2 * b + 1]);
+    }
+}
+
+// Epilogue of one finished row: the thresholded bits of row r are parked in lane r
+// (written after the last row), integers and logits are stored at once.
+template <int EPI, int TILES>
+__device__ __forceinline__ void f32_finish_row(int r, int64_t row, bool row_ok, int lane,
+                                               const int (&acc)[TILES], int32_t K, int ct0,
+                                               const bool (&c_ok)[TILES],
+                                               const int32_t (&tc)[TILES],
+                                               const float (&al)[TILES], uint64_t (&mine)[TILES],
+                                               void *__restrict__ out, int64_t out_stride)
+{
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+        const int c = (ct0 + t) * 64 + lane;
+        const int32_t z = K - 2 * acc[t];
+        if (EPI == BITGNN_EPI_THRESH_BITS) {
+            const uint64_t m = __ballot(c_ok[t] && z >= tc[t]);
+            if (lane == r)
+                mine[t] = m;
+        } else if (EPI == BITGNN_EPI_RAW_I32) {
+            if (c_ok[t] && row_ok)
+                ((int32_t *)out)[row * out_stride + c] = z;
+        } else {
+            if (c_ok[t] && row_ok)
+                ((float *)out)[row * out_stride + c] = al[t] * (float)z;
+        }
+    }
+}
+
+// SINGLE: all of K fits one register chunk, so a row is finished as soon as it has been
+// read and no per-row accumulators are kept.
+template <int EPI, int TILES, bool HAS_TAU, bool SINGLE>
 __global__ __launch_bounds__(kWaves * 64) void bgemm_f32_kernel(
     const float *__restrict__ x, int64_t n, int32_t K, int64_t ldx, const float *__restrict__ tau,
     int32_t kw32, const uint32_t *__restrict__ w32, int32_t M, int64_t w_stride32,
     const int32_t *__restrict__ T, const float *__restrict__ alpha, void *__restrict__ out,
     int64_t out_stride)
 {
+    constexpr int kWords = f32_chunk<TILES>::words;
+    constexpr int kVotes = kWords / 2;
+    constexpr int kAccRows = SINGLE ? 2 : kRowsF;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * kRowsF;
@@ -124,81 +192,80 @@ __global__ __launch_bounds__(kWaves * 64) void bgemm_f32_kernel(
     const int ct0 = blockIdx.y * TILES;
     const uint32_t *wrow[TILES];
     bool c_ok[TILES];
+    int32_t tc[TILES];
+    float al[TILES];
+    uint64_t mine[TILES];
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
         const int c = (ct0 + t) * 64 + lane;
         c_ok[t] = c < M;
         wrow[t] = w32 + (int64_t)(c_ok[t] ? c : 0) * w_stride32;
+        tc[t] = (EPI == BITGNN_EPI_THRESH_BITS && c_ok[t]) ? T[c] : 0;
+        al[t] = (EPI == BITGNN_EPI_SCALE_F32 && c_ok[t]) ? alpha[c] : 0.0f;
+        mine[t] = 0;
     }
-    int acc[kRowsF][TILES];
+    int acc[kAccRows][TILES];
 #pragma unroll
-    for (int r = 0; r < kRowsF; ++r)
+    for (int r = 0; r < kAccRows; ++r)
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
             acc[r][t] = 0;
+    const int64_t last = n - 1;
 
-    for (int k0 = 0; k0 < kw32; k0 += kChunk) { // 8 words of 32 bits = 4 votes of 64 floats
-        uint32_t wv[TILES][kChunk];
+    for (int k0 = 0; k0 < kw32; k0 += kWords) {
+        // weight words of the chunk (the bound is wave-uniform: scalar branches, no waits)
+        uint32_t wv[TILES][kWords];
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
 #pragma unroll
-            for (int j = 0; j < kChunk; ++j)
+            for (int j = 0; j < kWords; ++j)
                 wv[t][j] = (k0 + j < kw32) ? wrow[t][k0 + j] : 0u;
+        int32_t kc[kVotes];
+        float tv[kVotes];
+        uint64_t okmask[kVotes];
 #pragma unroll
-        for (int b = 0; b < kChunk / 2; ++b) {
+        for (int b = 0; b < kVotes; ++b) {
             const int32_t k = k0 * 32 + b * 64 + lane;
-            const bool ok = k < K;
-            const int32_t kc = ok ? k : K - 1; // clamped: the loads below are unconditional,
-            const float tv = HAS_TAU ? tau[kc] : 0.0f; // so all 16 are in flight together
-            float v[kRowsF];
+            okmask[b] = __ballot(k < K);
+            kc[b] = k < K ? k : K - 1; // clamped: no load is conditional
+            tv[b] = HAS_TAU ? tau[kc[b]] : 0.0f;
+        }
+        // rows one after the other, the next row requested before the current is consumed
+        float va[kVotes], vb[kVotes];
+        f32_load_row<kVotes, HAS_TAU>(x + (row0 < last ? row0 : last) * ldx, kc, va);
 #pragma unroll
-            for (int r = 0; r < kRowsF; ++r) {
-                const int64_t row = (row0 + r < n) ? row0 + r : n - 1; // wave-uniform
-                v[r] = x[row * ldx + kc];
+        for (int r = 0; r < kRowsF; r += 2) {
+            const int ra = SINGLE ? 0 : r, rb = SINGLE ? 1 : r + 1;
+            const int64_t r1 = row0 + r + 1 < last ? row0 + r + 1 : last; // wave-uniform
+            f32_load_row<kVotes, HAS_TAU>(x + r1 * ldx, kc, vb);
+            f32_consume_row<kVotes, TILES, HAS_TAU>(va, tv, okmask, wv, acc[ra]);
+            if (r + 2 < kRowsF) {
+                const int64_t r2 = row0 + r + 2 < last ? row0 + r + 2 : last;
+                f32_load_row<kVotes, HAS_TAU>(x + r2 * ldx, kc, va);
             }
-#pragma unroll
-            for (int r = 0; r < kRowsF; ++r) {
-                // beyond K the vote is 0 and so are the weight words: nothing is added
-                const uint64_t m = __ballot(ok && v[r] >= tv);
-                const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+            f32_consume_row<kVotes, TILES, HAS_TAU>(vb, tv, okmask, wv, acc[rb]);
+            if (SINGLE) {
+                f32_finish_row<EPI, TILES>(r, row0 + r, row0 + r < n, lane, acc[0], K, ct0, c_ok,
+                                           tc, al, mine, out, out_stride);
+                f32_finish_row<EPI, TILES>(r + 1, row0 + r + 1, row0 + r + 1 < n, lane, acc[1], K,
+                                           ct0, c_ok, tc, al, mine, out, out_stride);
 #pragma unroll
                 for (int t = 0; t < TILES; ++t)
-                    acc[r][t] += __popc(lo ^ wv[t][2 * b]) + __popc(hi ^ wv[t][2 * b + 1]);
+                    acc[0][t] = acc[1][t] = 0;
             }
         }
     }
-
+    if (!SINGLE) {
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        const int ct = ct0 + t;
-        const int c = ct * 64 + lane;
-        if (ct * 64 >= M)
-            break; // wave-uniform
-        if (EPI == BITGNN_EPI_THRESH_BITS) {
-            const int32_t tc = c_ok[t] ? T[c] : 0;
-            uint64_t mine = 0;
+        for (int r = 0; r < kRowsF; ++r)
+            f32_finish_row<EPI, TILES>(r, row0 + r, row0 + r < n, lane, acc[r], K, ct0, c_ok, tc,
+                                       al, mine, out, out_stride);
+    }
+    if (EPI == BITGNN_EPI_THRESH_BITS) {
 #pragma unroll
-            for (int r = 0; r < kRowsF; ++r) {
-                const int32_t z = K - 2 * acc[r][t];
-                const uint64_t m = __ballot(c_ok[t] && z >= tc);
-                if (lane == r)
-                    mine = m;
-            }
-            if (lane < kRowsF && row0 + lane < n)
-                ((uint64_t *)out)[(row0 + lane) * out_stride + ct] = mine;
-        } else if (EPI == BITGNN_EPI_RAW_I32) {
-#pragma unroll
-            for (int r = 0; r < kRowsF; ++r)
-                if (c_ok[t] && row0 + r < n)
-                    ((int32_t *)out)[(row0 + r) * out_stride + c] = K - 2 * acc[r][t];
-        } else {
-            const float a = c_ok[t] ? alpha[c] : 0.0f;
-#pragma unroll
-            for (int r = 0; r < kRowsF; ++r)
-                if (c_ok[t] && row0 + r < n)
-                    ((float *)out)[(row0 + r) * out_stride + c] =
-                        a * (float)(K - 2 * acc[r][t]);
-        }
+        for (int t = 0; t < TILES; ++t)
+            if ((ct0 + t) * 64 < M && lane < kRowsF && row0 + lane < n)
+                ((uint64_t *)out)[(row0 + lane) * out_stride + ct0 + t] = mine[t];
     }
 }
 
@@ -208,12 +275,22 @@ void launch_bgemm_f32(hipStream_t s, dim3 grid, const float *x, int64_t n, int32
                       int64_t w_stride32, const int32_t *T, const float *alpha, void *out,
                       int64_t out_stride)
 {
-    if (tau)
-        bgemm_f32_kernel<EPI, TILES, true><<<grid, kWaves * 64, 0, s>>>(
-            x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);
-    else
-        bgemm_f32_kernel<EPI, TILES, false><<<grid, kWaves * 64, 0, s>>>(
-            x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);
+#define BG_F32(TAU, SINGLE)                                                                       \
+    bgemm_f32_kernel<EPI, TILES, TAU, SINGLE><<<grid, kWaves * 64, 0, s>>>(                       \
+        x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride)
+    const bool single = kw32 <= f32_chunk<TILES>::words;
+    if (tau) {
+        if (single)
+            BG_F32(true, true);
+        else
+            BG_F32(true, false);
+    } else {
+        if (single)
+            BG_F32(false, true);
+        else
+            BG_F32(false, false);
+    }
+#undef BG_F32
 }
 
 template <int EPI>

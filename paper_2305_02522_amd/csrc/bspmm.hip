@@ -247,7 +247,7 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
 // Each lane writes its partial planes; the merge kernel adds the parts of a
 // node, applies the seed and the threshold (or unpacks the integers).
 constexpr int kPartPlanes = 10;
-constexpr int kBlkThreads = 1024;
+constexpr int kBlkThreads = 64 * kSlicesPerWg;
 
 constexpr int kPendLow = 3; // a block of 8 gathers produces one carry of weight 2^3
 constexpr int kPendTop = 6; // levels 3..5 park a carry; above, carries ripple (rare)

@@ -53,13 +53,19 @@ static inline void bg_time_end(bitgnn_ctx *ctx, hipStream_t s)
 static const int kGroupSteps = BITGNN_GROUP_STEPS;
 static_assert(kGroupSteps == 8 || kGroupSteps == 16, "groups of 8 or 16 steps");
 
+// Slices (wavefronts) per workgroup of the blocked bit-SpMM.
+#ifndef BITGNN_SLICES_PER_WG
+#define BITGNN_SLICES_PER_WG 16
+#endif
+static const int kSlicesPerWg = BITGNN_SLICES_PER_WG;
+
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
     int32_t ncb;            // column blocks
     uint32_t n_vrows;       // V: row parts ("virtual rows")
     uint32_t n_slices;      // ceil(V / 64)
-    uint32_t n_wgs;         // ceil(slices / 16)
+    uint32_t n_wgs;         // ceil(slices / kSlicesPerWg)
     uint32_t n_tiles;       // (slice, column block) tiles
     uint32_t n_groups;      // groups of kGroupSteps gather steps over all tiles
     uint32_t *wg_order;     // [n_wgs] workgroups by decreasing estimated work
