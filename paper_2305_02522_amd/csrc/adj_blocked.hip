@@ -277,7 +277,12 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     BG_HIP(ctx, keys_a.alloc((size_t)sort_n * 8));
     BG_HIP(ctx, keys_b.alloc((size_t)sort_n * 8));
     BG_HIP(ctx, hist.alloc((size_t)256 * sort_tiles * 4));
-    BG_HIP(ctx, scan_ws.alloc(scan_ws_words((uint64_t)256 * sort_tiles) * 4));
+    // one workspace for the scans of the sort histograms, of the n + 1 row counters and of
+    // the slice counters (S + 1 <= sort_n / 32 + 2); the tile scan gets its own below
+    const uint64_t scan_max = (uint64_t)256 * sort_tiles > (uint64_t)n + 1
+                                  ? (uint64_t)256 * sort_tiles
+                                  : (uint64_t)n + 1;
+    BG_HIP(ctx, scan_ws.alloc(scan_ws_words(scan_max) * 4));
 
     slot_kernel<<<blocks_for((int64_t)n + 1, 256), 256, 0, s>>>(
         adj->order, adj->deg, n, part_len, rank.as<int32_t>(), deg_sorted.as<uint32_t>(),
@@ -338,7 +343,11 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                         sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
                                         nullptr);
     BG_LAUNCH_CHECK(ctx, "tile count");
-    scan_inplace(tile_group.as<uint32_t>(), T + 1, scan_ws.as<uint32_t>(), s);
+    // the number of tiles is not bounded by the sizes above (sparse rows that span many
+    // column blocks): size the workspace of this scan by itself
+    DevBuf tile_scan_ws;
+    BG_HIP(ctx, tile_scan_ws.alloc(scan_ws_words((uint64_t)T + 1) * 4));
+    scan_inplace(tile_group.as<uint32_t>(), T + 1, tile_scan_ws.as<uint32_t>(), s);
     uint32_t G = 0;
     BG_HIP(ctx, hipMemcpyAsync(&G, tile_group.as<uint32_t>() + T, 4, hipMemcpyDeviceToHost, s));
     BG_HIP(ctx, hipStreamSynchronize(s));

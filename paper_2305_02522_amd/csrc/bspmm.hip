@@ -541,73 +541,192 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
 // Output layer in aggregate-then-transform order, fused with the merge:
 //   logits[i][c] = alpha[c] * sum_k S[i][k] * w[k][c],  S = 2 cnt - deg  (K <= 128)
 // which equals the paper's MM.BBF + BSpMM.FBF order exactly in integers because no
-// non-linearity sits between the two products.  The counts never leave their
-// bit-sliced form: with b the weight bits of class c (w = 2b - 1),
-//   sum_k S_k w_kc = 4 A_c - 2 deg popc(b_c) - 2 B + deg K,
-//   A_c = sum_p 2^p popc(plane_p & b_c),  B = sum_p 2^p popc(plane_p).
-// 4 lanes per node, one 32-channel word each; quad sums via DPP.
-__device__ __forceinline__ int32_t quad_sum(int32_t v)
+// non-linearity sits between the two products.  With wsum_c = sum_k w[k][c],
+//   sum_k S_k w_kc = 2 sum_k cnt_k w_kc - deg wsum_c,
+// and sum_k cnt_k w_kc is a small dense integer contraction (nodes x K x classes): it runs
+// on the matrix cores.  The bit-sliced counts of a node are turned into 7-bit digits
+// (base 128, so every digit is a non-negative int8) by 8x8 bit transposes, the weights
+// are +-1 bytes (0 beyond K or M), and one v_mfma_i32_16x16x32_i8 per digit, class tile
+// and 32-channel word accumulates 16 nodes x 16 classes.  The digits recombine by shifts.
+//
+// Lane roles in a wavefront of 16 nodes:
+//   merge:  lane = node * 4 + word   (sums the node's parts, as the plain merge does)
+//   digits: lane = node + 16 * g     (8 channels 8g..8g+7 of every word: the B operand)
+//   result: lane = node + 16 * g     holds classes 16 tile + 4 g + (0..3)
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// +-1 bytes of the class weights, rows padded to 128 channels and to a multiple of 16
+// classes, plus the column sums; written per call into the workspace (a few KB).
+__global__ void project_weights_kernel(const uint32_t *__restrict__ w32, int64_t w_stride32,
+                                       int32_t K, int32_t M, int32_t Mpad,
+                                       int8_t *__restrict__ w8, int32_t *__restrict__ wsum)
 {
-    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true); // lanes ^1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true); // lanes ^2
-    return v;
+    const int c = blockIdx.x, k = threadIdx.x; // 128 threads
+    int v = 0;
+    if (c < M && k < K)
+        v = ((w32[(int64_t)c * w_stride32 + (k >> 5)] >> (k & 31)) & 1u) ? 1 : -1;
+    w8[c * 128 + k] = (int8_t)v;
+    // column sum: two wavefronts, combined through LDS
+    __shared__ int part[2];
+    int sum = v;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        sum += __shfl_xor(sum, d, 64);
+    if ((k & 63) == 0)
+        part[k >> 6] = sum;
+    __syncthreads();
+    if (k == 0)
+        wsum[c] = part[0] + part[1];
+    (void)Mpad;
 }
 
-template <int P>
-__global__ __launch_bounds__(kBlock) void bspmm_merge_project_kernel(
+// 8x8 bit transpose of the 64-bit matrix (hi:lo), row r = byte r: three delta swaps.
+__device__ __forceinline__ void transpose8x8(uint32_t &lo, uint32_t &hi)
+{
+    uint32_t t;
+    t = (lo ^ (lo >> 7)) & 0x00AA00AAu;
+    lo ^= t ^ (t << 7);
+    t = (hi ^ (hi >> 7)) & 0x00AA00AAu;
+    hi ^= t ^ (t << 7);
+    t = (lo ^ (lo >> 14)) & 0x0000CCCCu;
+    lo ^= t ^ (t << 14);
+    t = (hi ^ (hi >> 14)) & 0x0000CCCCu;
+    hi ^= t ^ (t << 14);
+    t = (lo ^ ((lo >> 28) | (hi << 4))) & 0xF0F0F0F0u; // 64-bit shift by 28, low half
+    lo ^= t;
+    hi ^= t >> 4; // (t << 28) lands in the high half only: t has no bits below bit 4
+}
+
+constexpr int kProjWaves = 4;     // wavefronts per workgroup, 16 nodes each
+constexpr int kProjTiles = 4;     // class tiles of 16 per pass (64 classes)
+
+template <int NB> // digits of 7 bits: max degree < 2^(7 NB)
+__global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
     const uint32_t *__restrict__ part_pos, const int32_t *__restrict__ order,
-    const int32_t *__restrict__ deg, uint32_t n, int32_t K, int32_t W32,
-    const uint32_t *__restrict__ w32, int64_t w_stride32, int32_t M,
-    const float *__restrict__ alpha, float *__restrict__ out, int64_t ldo)
+    const int32_t *__restrict__ deg, uint32_t n, int32_t W32, const int8_t *__restrict__ w8,
+    const int32_t *__restrict__ wsum, int32_t M, const float *__restrict__ alpha,
+    float *__restrict__ out, int64_t ldo)
 {
-    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
-    const uint32_t slot_raw = t >> 2;
-    const int q = t & 3;
-    const bool live = slot_raw < n; // whole quads are live or dead together
-    const uint32_t slot = live ? slot_raw : 0u;
-    const bool has_word = live && q < W32;
-    const uint32_t row = (uint32_t)order[slot];
-    const int32_t d = deg[row];
-    uint32_t acc[P];
+    constexpr int P = 7 * NB;
+    constexpr int kAdd = P < kPartPlanes ? P : kPartPlanes; // planes a part can fill
+    __shared__ uint32_t s_planes[kProjWaves][16][4][P + 1];
+    __shared__ float s_out[kProjWaves][16][kProjTiles * 16 + 1];
+    __shared__ int32_t s_deg[kProjWaves][16];
+    __shared__ uint32_t s_row[kProjWaves][16];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t slot0 = (blockIdx.x * kProjWaves + wave) * 16;
+
+    // --- merge the parts of 16 nodes (lane = node * 4 + word)
+    {
+        const int node = lane >> 2, q = lane & 3;
+        const uint32_t slot_raw = slot0 + node;
+        const bool live = slot_raw < n;
+        const uint32_t slot = live ? slot_raw : 0u;
+        const uint32_t row = (uint32_t)order[slot];
+        uint32_t acc[P];
 #pragma unroll
-    for (int p = 0; p < P; ++p)
-        acc[p] = 0u;
-    if (has_word) {
-        const uint32_t v1 = row_vptr[slot + 1];
-        for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
-            const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
-            uint32_t carry = 0;
+        for (int p = 0; p < P; ++p)
+            acc[p] = 0u;
+        if (live && q < W32) {
+            const uint32_t v1 = row_vptr[slot + 1];
+            for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
+                const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
+                uint32_t carry = 0;
 #pragma unroll
-            for (int p = 0; p < kPartPlanes; ++p) {
-                uint32_t nc;
-                csa(acc[p], pp[p * 4], carry, nc);
-                carry = nc;
-            }
+                for (int p = 0; p < kAdd; ++p) {
+                    uint32_t nc;
+                    csa(acc[p], pp[p * 4], carry, nc);
+                    carry = nc;
+                }
 #pragma unroll
-            for (int p = kPartPlanes; p < P; ++p) {
-                const uint32_t nc = acc[p] & carry;
-                acc[p] ^= carry;
-                carry = nc;
+                for (int p = kAdd; p < P; ++p) {
+                    const uint32_t nc = acc[p] & carry;
+                    acc[p] ^= carry;
+                    carry = nc;
+                }
             }
         }
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            s_planes[wave][node][q][p] = acc[p];
+        if (q == 0) {
+            s_deg[wave][node] = live ? deg[row] : 0;
+            s_row[wave][node] = live ? row : 0xFFFFFFFFu;
+        }
     }
-    int32_t bsum = 0;
+    __syncthreads();
+
+    // --- digits (lane = node + 16 g): B operands, 8 channels x NB digits per word
+    const int nd = lane & 15, g = lane >> 4;
+    long bop[4][NB];
+    {
+        const uint32_t sel01 = (uint32_t)g | ((uint32_t)(4 + g) << 8) | 0x0C0C0000u;
 #pragma unroll
-    for (int p = P - 1; p >= 0; --p)
-        bsum = (bsum << 1) + __popc(acc[p]);
-    const int64_t B = quad_sum(bsum);
-    for (int c = 0; c < M; ++c) {
-        const uint32_t wq = q < W32 ? w32[(int64_t)c * w_stride32 + q] : 0u;
-        int32_t a = 0;
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int p = P - 1; p >= 0; --p)
-            a = (a << 1) + __popc(acc[p] & wq);
-        const int64_t A = quad_sum(a);
-        const int64_t pc = quad_sum(__popc(wq));
-        if (live && q == (c & 3)) {
-            const int64_t y = 4 * A - 2 * (int64_t)d * pc - 2 * B + (int64_t)d * K;
-            out[(int64_t)row * ldo + c] = alpha[c] * (float)(int32_t)y;
+            for (int b = 0; b < NB; ++b) {
+                const uint32_t *pl = &s_planes[wave][nd][w][7 * b];
+                // byte g of planes 7b .. 7b+6: rows of an 8x8 bit matrix (row 7 is zero)
+                const uint32_t h01 = __builtin_amdgcn_perm(pl[1], pl[0], sel01);
+                const uint32_t h23 = __builtin_amdgcn_perm(pl[3], pl[2], sel01);
+                const uint32_t h45 = __builtin_amdgcn_perm(pl[5], pl[4], sel01);
+                const uint32_t h6 = (pl[6] >> (8 * g)) & 0xFFu;
+                uint32_t lo = __builtin_amdgcn_perm(h23, h01, 0x05040100u);
+                uint32_t hi = __builtin_amdgcn_perm(h6, h45, 0x05040100u);
+                transpose8x8(lo, hi); // now byte j = the digit of channel 8g + j
+                bop[w][b] = (long)(((uint64_t)hi << 32) | lo);
+            }
+    }
+    const int32_t d_nd = s_deg[wave][nd];
+
+    // --- contraction with the class weights, 64 classes per pass
+    for (int c0 = 0; c0 < M; c0 += kProjTiles * 16) {
+        v4i acc[kProjTiles][NB];
+#pragma unroll
+        for (int t = 0; t < kProjTiles; ++t)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                acc[t][b] = (v4i){0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < kProjTiles; ++t) {
+            if (c0 + t * 16 < M) { // wave-uniform; w8 rows are padded to a multiple of 16
+                const int8_t *wr = w8 + (int64_t)(c0 + t * 16 + nd) * 128 + 8 * g;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    if (w < W32) {
+                        const long a = *(const long *)(wr + 32 * w);
+#pragma unroll
+                        for (int b = 0; b < NB; ++b)
+                            acc[t][b] = __builtin_amdgcn_mfma_i32_16x16x32_i8(a, bop[w][b],
+                                                                              acc[t][b], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads(); // the staging tile of the previous pass has been written out
+#pragma unroll
+        for (int t = 0; t < kProjTiles; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int cl = t * 16 + 4 * g + j;
+                const int c = c0 + cl;
+                int32_t val = 0;
+#pragma unroll
+                for (int b = NB - 1; b >= 0; --b)
+                    val = (val << 7) + acc[t][b][j];
+                float y = 0.0f;
+                if (c < M)
+                    y = alpha[c] * (float)(2 * val - d_nd * wsum[c]);
+                s_out[wave][nd][cl] = y;
+            }
+        __syncthreads();
+        const int ncls = M - c0 < kProjTiles * 16 ? M - c0 : kProjTiles * 16;
+        for (int node = 0; node < 16; ++node) {
+            const uint32_t row = s_row[wave][node];
+            if (row != 0xFFFFFFFFu && lane < ncls)
+                out[(int64_t)row * ldo + c0 + lane] = s_out[wave][node][lane];
         }
     }
 }
@@ -754,12 +873,16 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     const bitgnn_blocked *b = adj->blk;
     const int32_t W32 = (K + 31) / 32;
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
-    const size_t part_bytes = (size_t)b->n_vrows * kPartPlanes * 16;
-    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
+    const size_t part_bytes = ((size_t)b->n_vrows * kPartPlanes * 16 + 255) & ~(size_t)255;
+    const int32_t Mpad = (M + 15) / 16 * 16;
+    const size_t w8_bytes = (size_t)Mpad * 128;
+    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)Mpad * 4);
     if (rc != BITGNN_OK)
         return rc;
     uint4 *hperm = (uint4 *)ctx->ws;
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
+    int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
+    int32_t *wsum = (int32_t *)(w8 + w8_bytes);
     const size_t lds = ((size_t)b->cbn + 1) * 16;
     BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -771,21 +894,23 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
         b->tile_group, (const uint32_t *)b->idx16, b->n_slices, b->n_vrows, partial);
     bg_time_end(ctx, s);
     BG_LAUNCH_CHECK(ctx, "bspmm_blk");
-    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
-    const uint32_t *w32 = (const uint32_t *)wbits;
-    // count planes only (no bias bit): max_degree < 2^P
-    int P = 12;
-    while ((1ll << P) <= adj->max_degree)
-        P += (P == 20) ? 6 : 4;
-#define BG_PROJECT(PP)                                                                            \
-    bspmm_merge_project_kernel<PP><<<grid, kBlock, 0, s>>>(                                      \
+    project_weights_kernel<<<Mpad, 128, 0, s>>>((const uint32_t *)wbits, w_stride * 2, K, M, Mpad,
+                                                w8, wsum);
+    BG_LAUNCH_CHECK(ctx, "project_weights");
+    const unsigned grid = (unsigned)((adj->n + kProjWaves * 16 - 1) / (kProjWaves * 16));
+    // digits of 7 bits: max_degree < 2^(7 NB)
+    int NB = 1;
+    while ((1ll << (7 * NB)) <= adj->max_degree)
+        ++NB;
+#define BG_PROJECT(NBV)                                                                           \
+    bspmm_merge_project_kernel<NBV><<<grid, kProjWaves * 64, 0, s>>>(                             \
         (const uint32_t *)partial, b->row_vptr, b->part_pos, adj->order, adj->deg,                \
-        (uint32_t)adj->n, K, W32, w32, w_stride * 2, M, alpha, logits, ldo)
-    switch (P) {
-    case 12: BG_PROJECT(12); break;
-    case 16: BG_PROJECT(16); break;
-    case 20: BG_PROJECT(20); break;
-    default: BG_PROJECT(26); break;
+        (uint32_t)adj->n, W32, w8, wsum, M, alpha, logits, ldo)
+    switch (NB) {
+    case 1: BG_PROJECT(1); break;
+    case 2: BG_PROJECT(2); break;
+    case 3: BG_PROJECT(3); break;
+    default: BG_PROJECT(4); break;
     }
 #undef BG_PROJECT
     BG_LAUNCH_CHECK(ctx, "bspmm_merge_project");

@@ -399,6 +399,47 @@ def test_gcn_out_layer_both_orders(B, ctx, tuned, n, e, K, M):
     adj.close()
 
 
+@pytest.mark.parametrize("n,e,K,M,kind", [
+    (120, 500, 33, 5, "sparse"),          # max degree < 2^7: one 7-bit digit
+    (20001, 30000, 128, 41, "star"),      # a row of 20,001: three digits
+    (2100000, 0, 96, 3, "star")])         # a row of 2.1 million: four digits
+def test_gcn_out_layer_digit_counts(B, ctx, n, e, K, M, kind):
+    """The fused output layer splits neighbour counts into base-128 digits: cover every
+    digit count (the random graphs above have two)."""
+    r = np.random.default_rng(n + K)
+    src, dst = W.random_graph(r, n, e) if e else (np.zeros(0, np.int32), np.zeros(0, np.int32))
+    if kind == "star":
+        src = np.concatenate([src, np.zeros(n - 1, dtype=np.int32)])
+        dst = np.concatenate([dst, np.arange(1, n, dtype=np.int32)])
+    B.ctx_set_tuning(ctx, 8192, 256, 0)   # blocked path whatever the density
+    try:
+        adj = B.adj_build(ctx, dev(src), dev(dst), len(src), n, SYM_LOOPS)
+    finally:
+        B.ctx_set_tuning(ctx, *TUNINGS["default"])
+    rp, col = orc.adjacency(src, dst, n, SYM_LOOPS)
+    assert adj.blocked_info()["parts"] > 0
+    if kind == "star":
+        assert adj.max_degree == n
+    else:
+        assert adj.max_degree < 128
+    v = W.pm1(r, (n, K))
+    w = W.pm1(r, (K, M))
+    one = np.ones(M, dtype=np.float32)
+    kw = (K + 63) // 64
+    tmp = torch.zeros((n, M), dtype=torch.int32, device="cuda")
+    out = torch.zeros((n, M), dtype=torch.float32, device="cuda")
+    B.gcn_out_layer(ctx, adj, _pack_host(v), kw, K, kw, _pack_host(np.ascontiguousarray(w.T)), M,
+                    kw, dev(one), tmp, out, M)
+    torch.cuda.synchronize()
+    ref = orc.gcn_out_layer(rp, col, v, w, one)
+    got = out.cpu().numpy()
+    if adj.max_degree * K < (1 << 24):    # integers below 2^24 are exact in float32
+        assert np.array_equal(got, ref)
+    else:
+        assert rel_close(got, ref)
+    adj.close()
+
+
 def test_forward_ops_equals_forward(B, ctx):
     for cfg, kw in ((4, {"n": 6000, "mean_deg": 120.0}), (3, {"n": 20000})):
         wl = W.make_workload(cfg, **kw)
