@@ -21,8 +21,8 @@
 //    parts form a slice (one wavefront, one part per lane), 16 slices a
 //    workgroup.  For every (slice, block) tile the ids are stored lane-
 //    interleaved in groups of kGroupSteps steps: group g holds
-//    idx16[(g*64+lane)*kGroupSteps+k], padded with the id `cbn`, which addresses
-//    an all-zero LDS row.  The groups of a slice are consecutive, so a wavefront
+//    idx16[(g*64+lane)*kGroupSteps+k], padded with ids cbn .. cbn+15, which address
+//    all-zero LDS rows.  The groups of a slice are consecutive, so a wavefront
 //    reads one contiguous stream; one padding group closes the array so that
 //    reading one group ahead is always in bounds.
 #include "prims.h"
@@ -138,8 +138,32 @@ __global__ __launch_bounds__(64) void slice_range_kernel(const uint64_t *__restr
     }
 }
 
+// Sixteen byte counters in two registers (dynamic index without spilling an array).
+struct cls16 {
+    uint64_t lo = 0, hi = 0;
+    __device__ __forceinline__ uint32_t get(uint32_t c) const
+    {
+        return (uint32_t)(((c & 8u) ? hi : lo) >> ((c & 7u) * 8u)) & 255u;
+    }
+    __device__ __forceinline__ void set(uint32_t c, uint32_t v)
+    {
+        const uint64_t m = ~(255ull << ((c & 7u) * 8u)), b = (uint64_t)v << ((c & 7u) * 8u);
+        if (c & 8u)
+            hi = (hi & m) | b;
+        else
+            lo = (lo & m) | b;
+    }
+};
+
 // per (slice, block) tile: steps = longest lane; FILL = false counts groups,
-// FILL = true writes the lane-interleaved ids
+// FILL = true writes the lane-interleaved ids.
+//
+// Order of a lane's ids inside a tile (free: the sum does not depend on it).  The LDS
+// serves a 16-byte gather of 16 consecutive lanes in one pass when the 16 rows fall into
+// different 16-byte bank groups, i.e. differ in (row mod 16).  So lane L wants, at step k,
+// a row of class (L + k) mod 16: an id goes to the first free step of its class, ids whose
+// class has no step left take any free step, and padding steps address the all-zero row
+// of the wanted class (rows cbn .. cbn + 15 of the staged block are zero).
 template <bool FILL>
 __global__ __launch_bounds__(64) void tile_kernel(
     const uint64_t *__restrict__ svkeys, uint32_t V, const uint32_t *__restrict__ v_beg,
@@ -148,7 +172,7 @@ __global__ __launch_bounds__(64) void tile_kernel(
     uint32_t *__restrict__ tile_group, uint16_t *__restrict__ idx16)
 {
     const uint32_t slice = blockIdx.x;
-    const int lane = threadIdx.x;
+    const uint32_t lane = threadIdx.x;
     const uint32_t pos = slice * 64 + lane;
     const uint64_t mask = (1ull << cbits) - 1;
     uint32_t ptr = 0, e = 0;
@@ -161,6 +185,7 @@ __global__ __launch_bounds__(64) void tile_kernel(
     const uint32_t t0 = sl_tile_base[slice];
     for (uint32_t cb = lo; cb <= hi; ++cb) {
         const uint64_t lim = (uint64_t)(cb + 1) * (uint32_t)cbn;
+        const uint64_t cb0 = (uint64_t)cb * (uint32_t)cbn;
         const uint32_t first = ptr;
         while (ptr < e && (skeys[ptr] & mask) < lim)
             ++ptr;
@@ -172,12 +197,38 @@ __global__ __launch_bounds__(64) void tile_kernel(
         } else {
             const uint32_t g0 = tile_group[t0 + cb - lo];
             const uint32_t steps = (tile_group[t0 + cb - lo + 1] - g0) * kGroupSteps;
-            for (uint32_t k = 0; k < steps; ++k) {
-                const uint32_t id =
-                    k < cnt ? (uint32_t)((skeys[first + k] & mask) - (uint64_t)cb * (uint32_t)cbn)
-                            : (uint32_t)cbn;
-                idx16[((uint64_t)(g0 + k / kGroupSteps) * 64 + lane) * kGroupSteps +
-                      (k % kGroupSteps)] = (uint16_t)id;
+            auto slot = [&](uint32_t k) -> uint16_t & {
+                return idx16[((uint64_t)(g0 + k / kGroupSteps) * 64 + lane) * kGroupSteps +
+                             (k % kGroupSteps)];
+            };
+            // steps of class c' = (id - lane) mod 16 are c', c' + 16, ...: how many ids of
+            // every class find one
+            cls16 used, run;
+            for (uint32_t j = 0; j < cnt; ++j) {
+                const uint32_t id = (uint32_t)((skeys[first + j] & mask) - cb0);
+                const uint32_t c = (id - lane) & 15u;
+                const uint32_t cap = c < steps ? (steps - c + 15u) >> 4 : 0u;
+                const uint32_t u = used.get(c);
+                if (u < cap)
+                    used.set(c, u + 1);
+            }
+            for (uint32_t k = 0; k < steps; ++k)
+                slot(k) = (uint16_t)((uint32_t)cbn + ((lane + k) & 15u));
+            uint32_t kfree = 0;
+            for (uint32_t j = 0; j < cnt; ++j) {
+                const uint32_t id = (uint32_t)((skeys[first + j] & mask) - cb0);
+                const uint32_t c = (id - lane) & 15u;
+                const uint32_t m = run.get(c);
+                uint32_t k;
+                if (m < used.get(c)) {
+                    run.set(c, m + 1);
+                    k = c + 16u * m;
+                } else { // no step of its class left: the next step no class claims
+                    while ((kfree >> 4) < used.get(kfree & 15u))
+                        ++kfree;
+                    k = kfree++;
+                }
+                slot(k) = (uint16_t)id;
             }
         }
     }
@@ -191,12 +242,13 @@ __global__ void tail_group_kernel(uint16_t *__restrict__ idx16, uint32_t G, int 
         idx16[(uint64_t)G * 64 * kGroupSteps + i] = (uint16_t)cbn;
 }
 
-__global__ void part_pos_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
-                                uint32_t *__restrict__ part_pos)
+// part id (row-major: the parts of a row are consecutive) of every processing position
+__global__ void part_vid_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
+                                uint32_t *__restrict__ part_vid)
 {
     const uint32_t pos = blockIdx.x * blockDim.x + threadIdx.x;
     if (pos < V)
-        part_pos[(uint32_t)svkeys[pos] & kVidMask] = pos;
+        part_vid[pos] = (uint32_t)svkeys[pos] & kVidMask;
 }
 
 __global__ void wg_range_kernel(const uint32_t *__restrict__ sl_cb, uint32_t S, uint32_t W,
@@ -251,7 +303,7 @@ void bg_free_blocked(bitgnn_blocked *b)
     (void)hipFree(b->tile_group);
     (void)hipFree(b->idx16);
     (void)hipFree(b->row_vptr);
-    (void)hipFree(b->part_pos);
+    (void)hipFree(b->part_vid);
     free(b);
 }
 
@@ -323,11 +375,11 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                   hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
 
     const uint32_t S = (V + 63) / 64, W = (S + kSlicesPerWg - 1) / kSlicesPerWg;
-    DevBuf sl_cb, sl_tile_base, wg_cb, part_pos;
+    DevBuf sl_cb, sl_tile_base, wg_cb, part_vid;
     BG_HIP(ctx, sl_cb.alloc((size_t)S * 4));
     BG_HIP(ctx, sl_tile_base.alloc(((size_t)S + 1) * 4));
     BG_HIP(ctx, wg_cb.alloc((size_t)W * 4));
-    BG_HIP(ctx, part_pos.alloc((size_t)V * 4));
+    BG_HIP(ctx, part_vid.alloc((size_t)V * 4));
     slice_range_kernel<<<S + 1, 64, 0, s>>>(svkeys, V, S, sl_cb.as<uint32_t>(),
                                             sl_tile_base.as<uint32_t>());
     scan_inplace(sl_tile_base.as<uint32_t>(), S + 1, scan_ws.as<uint32_t>(), s);
@@ -364,7 +416,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                        sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
                                        idx16.as<uint16_t>());
     BG_LAUNCH_CHECK(ctx, "tile fill");
-    part_pos_kernel<<<blocks_for(V, 256), 256, 0, s>>>(svkeys, V, part_pos.as<uint32_t>());
+    part_vid_kernel<<<blocks_for(V, 256), 256, 0, s>>>(svkeys, V, part_vid.as<uint32_t>());
     wg_range_kernel<<<blocks_for(W, 256), 256, 0, s>>>(sl_cb.as<uint32_t>(), S, W,
                                                       wg_cb.as<uint32_t>());
     BG_LAUNCH_CHECK(ctx, "wg_range");
@@ -385,6 +437,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     BG_REQUIRE(ctx, b, BITGNN_ERR_INVALID_ARG, "bitgnn_adj_build: out of host memory");
     b->cbn = cbn;
     b->ncb = (int32_t)ncb;
+    b->part_len = part_len;
     b->n_vrows = V;
     b->n_slices = S;
     b->n_wgs = W;
@@ -399,7 +452,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     b->tile_group = (uint32_t *)tile_group.release();
     b->idx16 = (uint16_t *)idx16.release();
     b->row_vptr = (uint32_t *)nparts.release();
-    b->part_pos = (uint32_t *)part_pos.release();
+    b->part_vid = (uint32_t *)part_vid.release();
     adj->blk = b;
     adj->device_bytes += b->device_bytes;
     return BITGNN_OK;

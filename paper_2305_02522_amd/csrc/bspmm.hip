@@ -246,7 +246,9 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
 // 10 planes x 128 channels.  Parts never exceed 1023 entries, so 10 planes do.
 // Each lane writes its partial planes; the merge kernel adds the parts of a
 // node, applies the seed and the threshold (or unpacks the integers).
-constexpr int kPartPlanes = 10;
+// Counter planes of a row part: 8 when parts have at most 255 entries (the partial
+// planes of a part are then exactly one 128-byte line), else 10 (up to 1023 entries).
+static int part_planes_for(const bitgnn_blocked *b) { return b->part_len <= 255 ? 8 : 10; }
 constexpr int kBlkThreads = 64 * kSlicesPerWg;
 
 constexpr int kPendLow = 3; // a block of 8 gathers produces one carry of weight 2^3
@@ -255,9 +257,8 @@ constexpr int kPendTop = 6; // levels 3..5 park a carry; above, carries ripple (
 // Adds a carry of weight 2^P0 into the counters.  Level p holds a parked carry iff
 // bit (p - kPendLow) of blk (the number of 8-step blocks consumed so far): a binary
 // counter, so the control flow is wave-uniform and every register index is static.
-template <int P0>
-__device__ __forceinline__ void blk_cascade(uint32_t (&acc)[kPartPlanes][4],
-                                            uint32_t (&pend)[kPartPlanes][4],
+template <int P0, int PP>
+__device__ __forceinline__ void blk_cascade(uint32_t (&acc)[PP][4], uint32_t (&pend)[PP][4],
                                             uint32_t (&carry)[4], uint32_t blk)
 {
     if constexpr (P0 < kPendTop) {
@@ -272,12 +273,12 @@ __device__ __forceinline__ void blk_cascade(uint32_t (&acc)[kPartPlanes][4],
                 csa(acc[P0][q], pend[P0][q], carry[q], nc);
                 carry[q] = nc;
             }
-            blk_cascade<P0 + 1>(acc, pend, carry, blk);
+            blk_cascade<P0 + 1, PP>(acc, pend, carry, blk);
         }
     } else {
         // ripple the carry through the upper planes (once per 2^(kPendTop-kPendLow) blocks)
 #pragma unroll
-        for (int p = kPendTop; p < kPartPlanes; ++p)
+        for (int p = kPendTop; p < PP; ++p)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const uint32_t nc = acc[p][q] & carry[q];
@@ -305,9 +306,10 @@ __global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_s
 
 // One block of 8 steps: gathers of 16-byte rows from LDS, added into the bit-sliced
 // counters through a carry-save tree (7 adders per 8 inputs and 32-channel word).
+template <int PP>
 __device__ __forceinline__ void blk_consume(const uint32_t (&id)[8], const uint4 *hblk,
-                                            uint32_t (&acc)[kPartPlanes][4],
-                                            uint32_t (&pend)[kPartPlanes][4], uint32_t blk)
+                                            uint32_t (&acc)[PP][4], uint32_t (&pend)[PP][4],
+                                            uint32_t blk)
 {
     uint32_t x[8][4];
 #pragma unroll
@@ -330,7 +332,7 @@ __device__ __forceinline__ void blk_consume(const uint32_t (&id)[8], const uint4
         csa(acc[1][q], t2, t3, f1);
         csa(acc[2][q], f0, f1, carry[q]); // weight 8
     }
-    blk_cascade<kPendLow>(acc, pend, carry, blk);
+    blk_cascade<kPendLow, PP>(acc, pend, carry, blk);
 }
 
 #ifdef BITGNN_PROFILE
@@ -361,13 +363,14 @@ __device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx
     return r;
 }
 
+template <int PP>
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_order,
     const uint32_t *__restrict__ wg_cb, const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
-    const uint32_t *__restrict__ tile_group, const uint32_t *__restrict__ idx, uint32_t S,
-    uint32_t V, uint4 *__restrict__ partial)
+    const uint32_t *__restrict__ tile_group, const uint32_t *__restrict__ idx,
+    const uint32_t *__restrict__ part_vid, uint32_t S, uint32_t V, uint4 *__restrict__ partial)
 {
-    extern __shared__ uint4 hblk[]; // cbn rows + one all-zero row
+    extern __shared__ uint4 hblk[]; // cbn rows + 16 all-zero rows (one per bank group)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #ifdef BITGNN_EXPERIMENT_NATURAL_ORDER
@@ -391,12 +394,12 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     // while group g is consumed, across tile boundaries and LDS refills alike.
     // Reading one group past the stream's end is in bounds (padding group).
     blk_ids nxt = blk_load_ids(idx, g, lane);
-    if (tid == 0)
-        hblk[cbn] = make_uint4(0u, 0u, 0u, 0u);
+    if (tid < 16)
+        hblk[cbn + tid] = make_uint4(0u, 0u, 0u, 0u);
 
-    uint32_t acc[kPartPlanes][4], pend[kPartPlanes][4];
+    uint32_t acc[PP][4], pend[PP][4];
 #pragma unroll
-    for (int p = 0; p < kPartPlanes; ++p)
+    for (int p = 0; p < PP; ++p)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             acc[p][q] = 0u;
@@ -458,7 +461,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
                 nxt = blk_load_ids(idx, g + 1, lane);
 #pragma unroll
                 for (int j = 0; j < kGroupSteps / 8; ++j) {
-                    blk_consume(id[j], hblk, acc, pend, blk);
+                    blk_consume<PP>(id[j], hblk, acc, pend, blk);
                     ++blk;
                 }
             }
@@ -481,7 +484,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     for (int q = 0; q < 4; ++q) {
         uint32_t carry = 0;
 #pragma unroll
-        for (int p = kPendLow; p < kPartPlanes; ++p) {
+        for (int p = kPendLow; p < PP; ++p) {
             const uint32_t pd =
                 (p < kPendTop && ((blk >> (p - kPendLow)) & 1u)) ? pend[p][q] : 0u;
             uint32_t nc;
@@ -489,20 +492,23 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             carry = nc;
         }
     }
+    // partial planes are filed under the part id, so that the merge reads the parts of a
+    // row, and of consecutive rows, back to back
     const uint32_t pos = slice * 64 + lane;
     if (has && pos < V) {
+        const uint32_t vid = part_vid[pos];
 #pragma unroll
-        for (int p = 0; p < kPartPlanes; ++p)
-            partial[(uint64_t)pos * kPartPlanes + p] =
+        for (int p = 0; p < PP; ++p)
+            partial[(uint64_t)vid * PP + p] =
                 make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
     }
 }
 
 // 4 lanes per node (one per 32-channel word of the window): sum the node's parts.
-template <int P, int EPI>
+template <int P, int EPI, int PP>
 __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
     const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
-    const uint32_t *__restrict__ part_pos, const int32_t *__restrict__ order,
+    const int32_t *__restrict__ order,
     const int32_t *__restrict__ deg, uint32_t n, int win, int32_t C, int32_t W32,
     const uint32_t *__restrict__ seeds, void *__restrict__ out, int64_t out_stride)
 {
@@ -520,16 +526,16 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
         acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((d & 1u) * P + p) * W32 + w] : 0u;
     const uint32_t v1 = row_vptr[slot + 1];
     for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
-        const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
+        const uint32_t *pp = partial32 + ((uint64_t)v * PP) * 4 + q;
         uint32_t carry = 0;
 #pragma unroll
-        for (int p = 0; p < kPartPlanes; ++p) {
+        for (int p = 0; p < PP; ++p) {
             uint32_t nc;
             csa(acc[p], pp[p * 4], carry, nc);
             carry = nc;
         }
 #pragma unroll
-        for (int p = kPartPlanes; p < P; ++p) {
+        for (int p = PP; p < P; ++p) {
             const uint32_t nc = acc[p] & carry;
             acc[p] ^= carry;
             carry = nc;
@@ -600,16 +606,16 @@ __device__ __forceinline__ void transpose8x8(uint32_t &lo, uint32_t &hi)
 constexpr int kProjWaves = 4;     // wavefronts per workgroup, 16 nodes each
 constexpr int kProjTiles = 4;     // class tiles of 16 per pass (64 classes)
 
-template <int NB> // digits of 7 bits: max degree < 2^(7 NB)
+template <int NB, int PP> // digits of 7 bits: max degree < 2^(7 NB)
 __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
-    const uint32_t *__restrict__ part_pos, const int32_t *__restrict__ order,
+    const int32_t *__restrict__ order,
     const int32_t *__restrict__ deg, uint32_t n, int32_t W32, const int8_t *__restrict__ w8,
     const int32_t *__restrict__ wsum, int32_t M, const float *__restrict__ alpha,
     float *__restrict__ out, int64_t ldo)
 {
     constexpr int P = 7 * NB;
-    constexpr int kAdd = P < kPartPlanes ? P : kPartPlanes; // planes a part can fill
+    constexpr int kAdd = P < PP ? P : PP; // planes a part can fill
     __shared__ uint32_t s_planes[kProjWaves][16][4][P + 1];
     __shared__ float s_out[kProjWaves][16][kProjTiles * 16 + 1];
     __shared__ int32_t s_deg[kProjWaves][16];
@@ -632,7 +638,7 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
         if (live && q < W32) {
             const uint32_t v1 = row_vptr[slot + 1];
             for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
-                const uint32_t *pp = partial32 + ((uint64_t)part_pos[v] * kPartPlanes) * 4 + q;
+                const uint32_t *pp = partial32 + ((uint64_t)v * PP) * 4 + q;
                 uint32_t carry = 0;
 #pragma unroll
                 for (int p = 0; p < kAdd; ++p) {
@@ -731,21 +737,58 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     }
 }
 
+template <int P, int PP>
+void launch_merge_pp(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
+                     int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
+                     int64_t out_stride)
+{
+    const bitgnn_blocked *b = adj->blk;
+    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
+    if (epilogue == BITGNN_EPI_THRESH_BITS)
+        bspmm_merge_kernel<P, BITGNN_EPI_THRESH_BITS, PP><<<grid, kBlock, 0, s>>>(
+            partial32, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n, win, C,
+            W32, seeds, out, out_stride);
+    else
+        bspmm_merge_kernel<P, BITGNN_EPI_RAW_I32, PP><<<grid, kBlock, 0, s>>>(
+            partial32, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n, win, C,
+            W32, seeds, out, out_stride);
+}
+
 template <int P>
 void launch_merge_p(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
                     int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
                     int64_t out_stride)
 {
-    const bitgnn_blocked *b = adj->blk;
-    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
-    if (epilogue == BITGNN_EPI_THRESH_BITS)
-        bspmm_merge_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid, kBlock, 0, s>>>(
-            partial32, b->row_vptr, b->part_pos, adj->order, adj->deg, (uint32_t)adj->n, win, C,
-            W32, seeds, out, out_stride);
+    if (part_planes_for(adj->blk) == 8)
+        launch_merge_pp<P, 8>(s, epilogue, adj, partial32, win, C, W32, seeds, out, out_stride);
     else
-        bspmm_merge_kernel<P, BITGNN_EPI_RAW_I32><<<grid, kBlock, 0, s>>>(
-            partial32, b->row_vptr, b->part_pos, adj->order, adj->deg, (uint32_t)adj->n, win, C,
-            W32, seeds, out, out_stride);
+        launch_merge_pp<P, 10>(s, epilogue, adj, partial32, win, C, W32, seeds, out, out_stride);
+}
+
+// The aggregation kernel proper; `partial` receives PP planes of 16 bytes per part.
+static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint4 *hperm,
+                      uint4 *partial)
+{
+    const bitgnn_blocked *b = adj->blk;
+    const size_t lds = ((size_t)b->cbn + 16) * 16;
+#define BG_BLK(PPV)                                                                               \
+    do {                                                                                          \
+        BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel<PPV>,                      \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
+        bg_time_begin(ctx, s);                                                                    \
+        bspmm_blk_kernel<PPV><<<b->n_wgs, kBlkThreads, lds, s>>>(                                 \
+            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb,           \
+            b->sl_tile_base, b->tile_group, (const uint32_t *)b->idx16, b->part_vid, b->n_slices, \
+            b->n_vrows, partial);                                                                 \
+        bg_time_end(ctx, s);                                                                      \
+    } while (0)
+    if (part_planes_for(b) == 8)
+        BG_BLK(8);
+    else
+        BG_BLK(10);
+#undef BG_BLK
+    BG_LAUNCH_CHECK(ctx, "bspmm_blk");
+    return BITGNN_OK;
 }
 
 } // namespace
@@ -822,25 +865,19 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     if (rc != BITGNN_OK)
         return rc;
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
-    const size_t part_bytes = (size_t)b->n_vrows * kPartPlanes * 16;
+    const size_t part_bytes = (size_t)b->n_vrows * part_planes_for(b) * 16;
     rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
     if (rc != BITGNN_OK)
         return rc;
     uint4 *hperm = (uint4 *)ctx->ws;
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
-    const size_t lds = ((size_t)b->cbn + 1) * 16;
-    BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     const uint32_t *h32 = (const uint32_t *)hbits;
     for (int win = 0; win * 4 < W32; ++win) {
         blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
             h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm);
-        bg_time_begin(ctx, s);
-        bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
-            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
-            b->tile_group, (const uint32_t *)b->idx16, b->n_slices, b->n_vrows, partial);
-        bg_time_end(ctx, s);
-        BG_LAUNCH_CHECK(ctx, "bspmm_blk");
+        rc = launch_blk(ctx, s, adj, hperm, partial);
+        if (rc != BITGNN_OK)
+            return rc;
         switch (P) {
         case 12:
             launch_merge_p<12>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
@@ -873,7 +910,8 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     const bitgnn_blocked *b = adj->blk;
     const int32_t W32 = (K + 31) / 32;
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
-    const size_t part_bytes = ((size_t)b->n_vrows * kPartPlanes * 16 + 255) & ~(size_t)255;
+    const size_t part_bytes =
+        ((size_t)b->n_vrows * part_planes_for(b) * 16 + 255) & ~(size_t)255;
     const int32_t Mpad = (M + 15) / 16 * 16;
     const size_t w8_bytes = (size_t)Mpad * 128;
     int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)Mpad * 4);
@@ -883,17 +921,11 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
     int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
     int32_t *wsum = (int32_t *)(w8 + w8_bytes);
-    const size_t lds = ((size_t)b->cbn + 1) * 16;
-    BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
         (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm);
-    bg_time_begin(ctx, s);
-    bspmm_blk_kernel<<<b->n_wgs, kBlkThreads, lds, s>>>(
-        hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb, b->sl_tile_base,
-        b->tile_group, (const uint32_t *)b->idx16, b->n_slices, b->n_vrows, partial);
-    bg_time_end(ctx, s);
-    BG_LAUNCH_CHECK(ctx, "bspmm_blk");
+    rc = launch_blk(ctx, s, adj, hperm, partial);
+    if (rc != BITGNN_OK)
+        return rc;
     project_weights_kernel<<<Mpad, 128, 0, s>>>((const uint32_t *)wbits, w_stride * 2, K, M, Mpad,
                                                 w8, wsum);
     BG_LAUNCH_CHECK(ctx, "project_weights");
@@ -903,9 +935,16 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     while ((1ll << (7 * NB)) <= adj->max_degree)
         ++NB;
 #define BG_PROJECT(NBV)                                                                           \
-    bspmm_merge_project_kernel<NBV><<<grid, kProjWaves * 64, 0, s>>>(                             \
-        (const uint32_t *)partial, b->row_vptr, b->part_pos, adj->order, adj->deg,                \
-        (uint32_t)adj->n, W32, w8, wsum, M, alpha, logits, ldo)
+    do {                                                                                          \
+        if (part_planes_for(b) == 8)                                                              \
+            bspmm_merge_project_kernel<NBV, 8><<<grid, kProjWaves * 64, 0, s>>>(                  \
+                (const uint32_t *)partial, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n,   \
+                W32, w8, wsum, M, alpha, logits, ldo);                                            \
+        else                                                                                      \
+            bspmm_merge_project_kernel<NBV, 10><<<grid, kProjWaves * 64, 0, s>>>(                 \
+                (const uint32_t *)partial, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n,   \
+                W32, w8, wsum, M, alpha, logits, ldo);                                            \
+    } while (0)
     switch (NB) {
     case 1: BG_PROJECT(1); break;
     case 2: BG_PROJECT(2); break;

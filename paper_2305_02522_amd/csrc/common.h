@@ -63,6 +63,7 @@ static const int kSlicesPerWg = BITGNN_SLICES_PER_WG;
 struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
     int32_t ncb;            // column blocks
+    int32_t part_len;       // longest row part (sets the planes of the partial counters)
     uint32_t n_vrows;       // V: row parts ("virtual rows")
     uint32_t n_slices;      // ceil(V / 64)
     uint32_t n_wgs;         // ceil(slices / kSlicesPerWg)
@@ -76,7 +77,7 @@ struct bitgnn_blocked {
     uint16_t *idx16;        // [(n_groups + 1) * 64 * kGroupSteps] column ids inside the block;
                             // cbn = "none"; the last group is padding that a prefetch may read
     uint32_t *row_vptr;     // [n + 1] by degree-order slot: first part of the row
-    uint32_t *part_pos;     // [V] position of a part in the processing order
+    uint32_t *part_vid;     // [V] by processing position: part id (a row's parts are consecutive ids)
     size_t device_bytes;
 };
 

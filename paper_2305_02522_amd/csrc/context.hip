@@ -15,7 +15,7 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
         return BITGNN_ERR_INVALID_ARG;
     ctx->device = device;
     ctx->cb_nodes = 8192;
-    ctx->part_len = 256;
+    ctx->part_len = 255;
     ctx->min_avg_degree = 32;
     if (device >= 0) {
         int count = 0;

@@ -26,7 +26,7 @@ def ctx(B):
     c.close()
 
 
-TUNINGS = {"default": (8192, 256, 32), "csr-only": (8192, 256, 1 << 30),
+TUNINGS = {"default": (8192, 255, 32), "csr-only": (8192, 255, 1 << 30),
            "blocked-small": (128, 16, 0), "blocked-long-parts": (64, 1023, 0),
            "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0)}
 
@@ -146,7 +146,7 @@ def test_tuning_validation(B, ctx):
         with pytest.raises(B.BitgnnError) as e:
             B.ctx_set_tuning(ctx, *bad)
         assert e.value.code == B.ERR_INVALID_ARG
-    B.ctx_set_tuning(ctx, 8192, 256, 32)
+    B.ctx_set_tuning(ctx, *TUNINGS["default"])
 
 
 def test_adj_build_rejects_out_of_range(B, ctx):
