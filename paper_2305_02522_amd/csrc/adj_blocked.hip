@@ -282,12 +282,27 @@ __global__ void wg_cost_kernel(const uint32_t *__restrict__ wg_cb,
     keys[w] = ((0xFFFFFFFFull - min(cost, (uint64_t)0xFFFFFFFFull)) << 32) | w;
 }
 
-__global__ void wg_order_kernel(const uint64_t *__restrict__ keys, uint32_t W,
-                                uint32_t *__restrict__ wg_order)
+// What the aggregation kernel reads at its start, flattened so that it takes two
+// dependent loads instead of five: per dispatch position {workgroup, its block range},
+// per slice {its block range, first tile, first group}.
+__global__ void wg_item_kernel(const uint64_t *__restrict__ keys, uint32_t W,
+                               const uint32_t *__restrict__ wg_cb, uint2 *__restrict__ wg_item)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < W)
-        wg_order[i] = (uint32_t)keys[i];
+    if (i < W) {
+        const uint32_t w = (uint32_t)keys[i];
+        wg_item[i] = make_uint2(w, wg_cb[w]);
+    }
+}
+
+__global__ void slice_desc_kernel(const uint32_t *__restrict__ sl_cb,
+                                  const uint32_t *__restrict__ sl_tile_base,
+                                  const uint32_t *__restrict__ tile_group, uint32_t S,
+                                  uint4 *__restrict__ sl_desc)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < S)
+        sl_desc[i] = make_uint4(sl_cb[i], sl_tile_base[i], tile_group[sl_tile_base[i]], 0u);
 }
 
 } // namespace
@@ -296,10 +311,8 @@ void bg_free_blocked(bitgnn_blocked *b)
 {
     if (!b)
         return;
-    (void)hipFree(b->wg_order);
-    (void)hipFree(b->wg_cb);
-    (void)hipFree(b->sl_cb);
-    (void)hipFree(b->sl_tile_base);
+    (void)hipFree(b->wg_item);
+    (void)hipFree(b->sl_desc);
     (void)hipFree(b->tile_group);
     (void)hipFree(b->idx16);
     (void)hipFree(b->row_vptr);
@@ -421,16 +434,22 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                                       wg_cb.as<uint32_t>());
     BG_LAUNCH_CHECK(ctx, "wg_range");
     // dispatch order: heaviest workgroups first (the key buffers of the parts are free again)
-    DevBuf wg_order;
-    BG_HIP(ctx, wg_order.alloc((size_t)W * 4));
+    DevBuf wg_item, sl_desc;
+    BG_HIP(ctx, wg_item.alloc((size_t)W * 8));
+    BG_HIP(ctx, sl_desc.alloc((size_t)S * 16));
     wg_cost_kernel<<<blocks_for(W, 256), 256, 0, s>>>(wg_cb.as<uint32_t>(),
                                                      sl_tile_base.as<uint32_t>(),
                                                      tile_group.as<uint32_t>(), S, W,
                                                      vk_a.as<uint64_t>());
     uint64_t *wsorted = radix_sort(vk_a.as<uint64_t>(), vk_b.as<uint64_t>(), W, 64,
                                    hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
-    wg_order_kernel<<<blocks_for(W, 256), 256, 0, s>>>(wsorted, W, wg_order.as<uint32_t>());
-    BG_LAUNCH_CHECK(ctx, "wg_order");
+    wg_item_kernel<<<blocks_for(W, 256), 256, 0, s>>>(wsorted, W, wg_cb.as<uint32_t>(),
+                                                     wg_item.as<uint2>());
+    slice_desc_kernel<<<blocks_for(S, 256), 256, 0, s>>>(sl_cb.as<uint32_t>(),
+                                                        sl_tile_base.as<uint32_t>(),
+                                                        tile_group.as<uint32_t>(), S,
+                                                        sl_desc.as<uint4>());
+    BG_LAUNCH_CHECK(ctx, "wg_item / slice_desc");
     BG_HIP(ctx, hipStreamSynchronize(s));
 
     bitgnn_blocked *b = (bitgnn_blocked *)calloc(1, sizeof(bitgnn_blocked));
@@ -443,12 +462,10 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     b->n_wgs = W;
     b->n_tiles = T;
     b->n_groups = G;
-    b->device_bytes = ((size_t)G + 1) * kGroupIds * 2 + ((size_t)T + 1) * 4 + ((size_t)S * 2 + 1) * 4 +
-                      (size_t)W * 4 + ((size_t)n + 1) * 4 + (size_t)V * 4;
-    b->wg_order = (uint32_t *)wg_order.release();
-    b->wg_cb = (uint32_t *)wg_cb.release();
-    b->sl_cb = (uint32_t *)sl_cb.release();
-    b->sl_tile_base = (uint32_t *)sl_tile_base.release();
+    b->device_bytes = ((size_t)G + 1) * kGroupIds * 2 + ((size_t)T + 1) * 4 + (size_t)S * 16 +
+                      (size_t)W * 8 + ((size_t)n + 1) * 4 + (size_t)V * 4;
+    b->wg_item = (uint2 *)wg_item.release();
+    b->sl_desc = (uint4 *)sl_desc.release();
     b->tile_group = (uint32_t *)tile_group.release();
     b->idx16 = (uint16_t *)idx16.release();
     b->row_vptr = (uint32_t *)nparts.release();

@@ -365,30 +365,26 @@ __device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx
 
 template <int PP>
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
-    const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint32_t *__restrict__ wg_order,
-    const uint32_t *__restrict__ wg_cb, const uint32_t *__restrict__ sl_cb, const uint32_t *__restrict__ sl_tile_base,
-    const uint32_t *__restrict__ tile_group, const uint32_t *__restrict__ idx,
-    const uint32_t *__restrict__ part_vid, uint32_t S, uint32_t V, uint4 *__restrict__ partial)
+    const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint2 *__restrict__ wg_item,
+    const uint4 *__restrict__ sl_desc, const uint32_t *__restrict__ tile_group,
+    const uint32_t *__restrict__ idx, const uint32_t *__restrict__ part_vid, uint32_t S,
+    uint32_t V, uint4 *__restrict__ partial)
 {
     extern __shared__ uint4 hblk[]; // cbn rows + 16 all-zero rows (one per bank group)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef BITGNN_EXPERIMENT_NATURAL_ORDER
-    const uint32_t wg = blockIdx.x;
-#else
-    const uint32_t wg = wg_order[blockIdx.x]; // heaviest workgroups are dispatched first
-#endif
+    const uint2 item = wg_item[blockIdx.x]; // heaviest workgroups are dispatched first
+    const uint32_t wg = item.x;
     const uint32_t slice = wg * (kBlkThreads / 64) + wave;
     const bool has = slice < S;
-    const uint32_t wcb = wg_cb[wg];
-    const uint32_t wlo = wcb & 0xFFFFu, whi = wcb >> 16;
+    const uint32_t wlo = item.y & 0xFFFFu, whi = item.y >> 16;
     uint32_t mylo = 1, myhi = 0, t0 = 0, g = 0;
     if (has) {
-        const uint32_t c = sl_cb[slice];
-        mylo = c & 0xFFFFu;
-        myhi = c >> 16;
-        t0 = sl_tile_base[slice];
-        g = tile_group[t0];
+        const uint4 d = sl_desc[slice];
+        mylo = d.x & 0xFFFFu;
+        myhi = d.x >> 16;
+        t0 = d.y;
+        g = d.z;
     }
     // The groups of a slice are one contiguous stream: group g + 1 is requested
     // while group g is consumed, across tile boundaries and LDS refills alike.
@@ -413,6 +409,10 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
 #endif
 
     for (uint32_t cb = wlo; cb <= whi; ++cb) {
+        // end of this tile's groups: requested before the refill so that the scalar
+        // load's latency hides behind it
+        const bool mine = cb >= mylo && cb <= myhi; // wave-uniform
+        const uint32_t g1 = tile_group[mine ? t0 + cb - mylo + 1 : 0u];
         __syncthreads(); // all wavefronts are done with the previous block
 #ifdef BITGNN_PROFILE
         { const long long t = BLK_PROF_T(); p_comp += t - p_t0; p_t0 = t; }
@@ -443,8 +443,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
 #ifdef BITGNN_PROFILE
         { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
 #endif
-        if (cb >= mylo && cb <= myhi) { // wave-uniform
-            const uint32_t g1 = tile_group[t0 + cb - mylo + 1];
+        if (mine) {
             for (; g < g1; ++g) {
                 // Unpack the ids first and pin them in registers: after that
                 // `nxt` is dead, the next request reuses its registers without a copy, and
@@ -777,9 +776,8 @@ static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, con
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
         bg_time_begin(ctx, s);                                                                    \
         bspmm_blk_kernel<PPV><<<b->n_wgs, kBlkThreads, lds, s>>>(                                 \
-            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_order, b->wg_cb, b->sl_cb,           \
-            b->sl_tile_base, b->tile_group, (const uint32_t *)b->idx16, b->part_vid, b->n_slices, \
-            b->n_vrows, partial);                                                                 \
+            hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_item, b->sl_desc, b->tile_group,     \
+            (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, partial);           \
         bg_time_end(ctx, s);                                                                      \
     } while (0)
     if (part_planes_for(b) == 8)

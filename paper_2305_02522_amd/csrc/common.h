@@ -69,10 +69,9 @@ struct bitgnn_blocked {
     uint32_t n_wgs;         // ceil(slices / kSlicesPerWg)
     uint32_t n_tiles;       // (slice, column block) tiles
     uint32_t n_groups;      // groups of kGroupSteps gather steps over all tiles
-    uint32_t *wg_order;     // [n_wgs] workgroups by decreasing estimated work
-    uint32_t *wg_cb;        // [n_wgs] first column block | last << 16
-    uint32_t *sl_cb;        // [n_slices] first | last << 16
-    uint32_t *sl_tile_base; // [n_slices + 1]
+    uint2 *wg_item;         // [n_wgs] by decreasing estimated work: {workgroup,
+                            //         first column block | last << 16}
+    uint4 *sl_desc;         // [n_slices] {first block | last << 16, first tile, first group, 0}
     uint32_t *tile_group;   // [n_tiles + 1] prefix of group counts
     uint16_t *idx16;        // [(n_groups + 1) * 64 * kGroupSteps] column ids inside the block;
                             // cbn = "none"; the last group is padding that a prefetch may read
