@@ -288,11 +288,16 @@ __device__ __forceinline__ void blk_cascade(uint32_t (&acc)[PP][4], uint32_t (&p
     }
 }
 
+// Activation rows in degree order (one 128-channel window); also rewinds the work
+// counter of the aggregation kernel that follows on the same stream.
 __global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_stride32,
                                    const int32_t *__restrict__ order, uint32_t n, int w0,
-                                   int W32, uint4 *__restrict__ hperm)
+                                   int W32, uint4 *__restrict__ hperm,
+                                   uint32_t *__restrict__ queue)
 {
     const uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot == 0)
+        *queue = 0u;
     if (slot >= n)
         return;
     const uint32_t *r = h32 + (int64_t)order[slot] * h_stride32;
@@ -363,17 +368,31 @@ __device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx
     return r;
 }
 
+// Launched with one workgroup per compute unit (its LDS block leaves room for one
+// only).  Every workgroup takes work items (kSlicesPerWg slices each, heaviest first)
+// from an atomic counter until the list is exhausted: a compute unit that finishes
+// early picks up more work whatever the hardware's dispatch order is, and no time is
+// lost to launching workgroups in the middle of the kernel.
 template <int PP>
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint2 *__restrict__ wg_item,
     const uint4 *__restrict__ sl_desc, const uint32_t *__restrict__ tile_group,
     const uint32_t *__restrict__ idx, const uint32_t *__restrict__ part_vid, uint32_t S,
-    uint32_t V, uint4 *__restrict__ partial)
+    uint32_t V, uint32_t n_items, uint32_t *__restrict__ queue, uint4 *__restrict__ partial)
 {
     extern __shared__ uint4 hblk[]; // cbn rows + 16 all-zero rows (one per bank group)
+    __shared__ uint32_t s_next;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint2 item = wg_item[blockIdx.x]; // heaviest workgroups are dispatched first
+    if (tid < 16)
+        hblk[cbn + tid] = make_uint4(0u, 0u, 0u, 0u);
+    if (tid == 0)
+        s_next = atomicAdd(queue, 1u);
+    __syncthreads();
+    uint32_t cur = s_next;
+  while (cur < n_items) { // uniform over the workgroup: every wavefront leaves together
+    __syncthreads();      // everyone has read s_next
+    const uint2 item = wg_item[cur];
     const uint32_t wg = item.x;
     const uint32_t slice = wg * (kBlkThreads / 64) + wave;
     const bool has = slice < S;
@@ -390,8 +409,6 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     // while group g is consumed, across tile boundaries and LDS refills alike.
     // Reading one group past the stream's end is in bounds (padding group).
     blk_ids nxt = blk_load_ids(idx, g, lane);
-    if (tid < 16)
-        hblk[cbn + tid] = make_uint4(0u, 0u, 0u, 0u);
 
     uint32_t acc[PP][4], pend[PP][4];
 #pragma unroll
@@ -413,6 +430,11 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
         // load's latency hides behind it
         const bool mine = cb >= mylo && cb <= myhi; // wave-uniform
         const uint32_t g1 = tile_group[mine ? t0 + cb - mylo + 1 : 0u];
+        // the next item is drawn while the last block of this one is processed: late
+        // enough to go to whichever workgroup is about to be free, early enough to hide
+        // the round trip
+        if (cb == whi && tid == 0)
+            s_next = atomicAdd(queue, 1u);
         __syncthreads(); // all wavefronts are done with the previous block
 #ifdef BITGNN_PROFILE
         { const long long t = BLK_PROF_T(); p_comp += t - p_t0; p_t0 = t; }
@@ -472,7 +494,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     if (tid == 0 && g_blk_prof) {
         const long long t = clock64();
         p_comp += t - p_t0;
-        unsigned long long *o = g_blk_prof + 8ull * blockIdx.x;
+        unsigned long long *o = g_blk_prof + 8ull * cur;
         o[0] = p_start; o[1] = t; o[2] = p_fill; o[3] = p_comp;
         o[4] = p_wall0; o[5] = wall_clock64(); o[6] = __smid();
         o[7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)); /* XCC_ID */
@@ -501,6 +523,8 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             partial[(uint64_t)vid * PP + p] =
                 make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
     }
+    cur = s_next; // written before the barriers of the item's last block
+  }
 }
 
 // 4 lanes per node (one per 32-channel word of the window): sum the node's parts.
@@ -770,14 +794,17 @@ static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, con
 {
     const bitgnn_blocked *b = adj->blk;
     const size_t lds = ((size_t)b->cbn + 16) * 16;
+    const uint32_t cus = ctx->n_cus > 0 ? (uint32_t)ctx->n_cus : 256u;
+    const unsigned grid = b->n_wgs < cus ? b->n_wgs : cus;
 #define BG_BLK(PPV)                                                                               \
     do {                                                                                          \
         BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel<PPV>,                      \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
         bg_time_begin(ctx, s);                                                                    \
-        bspmm_blk_kernel<PPV><<<b->n_wgs, kBlkThreads, lds, s>>>(                                 \
+        bspmm_blk_kernel<PPV><<<grid, kBlkThreads, lds, s>>>(                                     \
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_item, b->sl_desc, b->tile_group,     \
-            (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, partial);           \
+            (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, b->n_wgs,           \
+            ctx->queue, partial);                                                                 \
         bg_time_end(ctx, s);                                                                      \
     } while (0)
     if (part_planes_for(b) == 8)
@@ -872,7 +899,7 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     const uint32_t *h32 = (const uint32_t *)hbits;
     for (int win = 0; win * 4 < W32; ++win) {
         blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
-            h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm);
+            h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm, ctx->queue);
         rc = launch_blk(ctx, s, adj, hperm, partial);
         if (rc != BITGNN_OK)
             return rc;
@@ -920,7 +947,8 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
     int32_t *wsum = (int32_t *)(w8 + w8_bytes);
     blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
-        (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm);
+        (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm,
+        ctx->queue);
     rc = launch_blk(ctx, s, adj, hperm, partial);
     if (rc != BITGNN_OK)
         return rc;

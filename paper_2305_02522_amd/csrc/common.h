@@ -13,6 +13,8 @@
 
 struct bitgnn_ctx {
     int device;           // -1: validation-only context
+    int n_cus;            // compute units of the device
+    uint32_t *queue;      // device word: work counter of the blocked bit-SpMM
     char err[256];
     uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
     size_t seed_table_words;

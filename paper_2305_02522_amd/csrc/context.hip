@@ -26,6 +26,10 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
         }
         e = hipSetDevice(device);
         if (e == hipSuccess)
+            e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (e == hipSuccess)
+            e = hipMalloc((void **)&ctx->queue, 256);
+        if (e == hipSuccess)
             e = hipMalloc((void **)&ctx->seed_table, kSeedTableWords * sizeof(uint32_t));
         if (e != hipSuccess) {
             free(ctx);
@@ -43,6 +47,8 @@ extern "C" void bitgnn_ctx_destroy(bitgnn_ctx *ctx)
         return;
     if (ctx->seed_table)
         (void)hipFree(ctx->seed_table);
+    if (ctx->queue)
+        (void)hipFree(ctx->queue);
     if (ctx->ws)
         (void)hipFree(ctx->ws);
     for (int i = 0; i < 2 * kMaxTimed; ++i)
