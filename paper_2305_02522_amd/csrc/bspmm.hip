@@ -368,11 +368,36 @@ __device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx
     return r;
 }
 
+// What a wavefront needs to know of a work item (all wave-uniform).
+struct blk_item {
+    uint32_t wlo, whi;   // column blocks the workgroup walks
+    uint32_t mylo, myhi; // column blocks of this wavefront's slice (mylo > myhi: none)
+    uint32_t t0, g;      // first tile, first group of the slice's id stream
+    uint32_t slice;
+    bool has;
+};
+__device__ __forceinline__ blk_item blk_item_of(uint2 it, uint4 d, uint32_t slice, bool has)
+{
+    blk_item r;
+    r.wlo = it.y & 0xFFFFu;
+    r.whi = it.y >> 16;
+    r.mylo = has ? (d.x & 0xFFFFu) : 1u;
+    r.myhi = has ? (d.x >> 16) : 0u;
+    r.t0 = has ? d.y : 0u;
+    r.g = has ? d.z : 0u;
+    r.slice = slice;
+    r.has = has;
+    return r;
+}
+
 // Launched with one workgroup per compute unit (its LDS block leaves room for one
 // only).  Every workgroup takes work items (kSlicesPerWg slices each, heaviest first)
 // from an atomic counter until the list is exhausted: a compute unit that finishes
 // early picks up more work whatever the hardware's dispatch order is, and no time is
-// lost to launching workgroups in the middle of the kernel.
+// lost to launching workgroups in the middle of the kernel.  The next item is drawn
+// while the last block of the current one is processed (late enough to go to whichever
+// workgroup is about to be free), and its descriptors and first ids are requested
+// step by step behind the barriers of that block, so the switch costs no round trip.
 template <int PP>
 __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint2 *__restrict__ wg_item,
@@ -390,141 +415,157 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
         s_next = atomicAdd(queue, 1u);
     __syncthreads();
     uint32_t cur = s_next;
-  while (cur < n_items) { // uniform over the workgroup: every wavefront leaves together
-    __syncthreads();      // everyone has read s_next
-    const uint2 item = wg_item[cur];
-    const uint32_t wg = item.x;
-    const uint32_t slice = wg * (kBlkThreads / 64) + wave;
-    const bool has = slice < S;
-    const uint32_t wlo = item.y & 0xFFFFu, whi = item.y >> 16;
-    uint32_t mylo = 1, myhi = 0, t0 = 0, g = 0;
-    if (has) {
-        const uint4 d = sl_desc[slice];
-        mylo = d.x & 0xFFFFu;
-        myhi = d.x >> 16;
-        t0 = d.y;
-        g = d.z;
+    if (cur >= n_items) // uniform over the workgroup
+        return;
+    blk_item it;
+    {
+        const uint2 w = wg_item[cur];
+        const uint32_t slice = w.x * kSlicesPerWg + wave;
+        const bool has = slice < S;
+        it = blk_item_of(w, sl_desc[has ? slice : 0u], slice, has);
     }
     // The groups of a slice are one contiguous stream: group g + 1 is requested
     // while group g is consumed, across tile boundaries and LDS refills alike.
     // Reading one group past the stream's end is in bounds (padding group).
-    blk_ids nxt = blk_load_ids(idx, g, lane);
+    blk_ids nxt = blk_load_ids(idx, it.g, lane);
 
-    uint32_t acc[PP][4], pend[PP][4];
+    for (;;) { // one work item per turn; every wavefront of the workgroup leaves together
+        __syncthreads(); // everyone has read s_next
+        uint32_t g = it.g;
+        const uint32_t pos = it.slice * 64 + lane;
+        const bool writes = it.has && pos < V;
+        const uint32_t vid = part_vid[writes ? pos : 0u]; // needed at the end only
+        uint32_t acc[PP][4], pend[PP][4];
 #pragma unroll
-    for (int p = 0; p < PP; ++p)
+        for (int p = 0; p < PP; ++p)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            acc[p][q] = 0u;
-            pend[p][q] = 0u;
-        }
-    uint32_t blk = 0; // blocks of 8 steps consumed by this wavefront
+            for (int q = 0; q < 4; ++q) {
+                acc[p][q] = 0u;
+                pend[p][q] = 0u;
+            }
+        uint32_t blk = 0; // blocks of 8 steps consumed by this wavefront
+        uint32_t nx = 0;  // the item after this one
+        uint2 nw = make_uint2(0u, 0u);
+        uint4 nd = make_uint4(0u, 0u, 0u, 0u);
+        uint32_t nslice = 0;
+        bool nhas = false;
 #ifdef BITGNN_PROFILE
-    const long long p_start = BLK_PROF_T();
-    const unsigned long long p_wall0 = (tid == 0) ? wall_clock64() : 0;
-    long long p_fill = 0, p_comp = 0, p_t0 = p_start;
+        const long long p_start = BLK_PROF_T();
+        const unsigned long long p_wall0 = (tid == 0) ? wall_clock64() : 0;
+        long long p_fill = 0, p_comp = 0, p_t0 = p_start;
 #endif
 
-    for (uint32_t cb = wlo; cb <= whi; ++cb) {
-        // end of this tile's groups: requested before the refill so that the scalar
-        // load's latency hides behind it
-        const bool mine = cb >= mylo && cb <= myhi; // wave-uniform
-        const uint32_t g1 = tile_group[mine ? t0 + cb - mylo + 1 : 0u];
-        // the next item is drawn while the last block of this one is processed: late
-        // enough to go to whichever workgroup is about to be free, early enough to hide
-        // the round trip
-        if (cb == whi && tid == 0)
-            s_next = atomicAdd(queue, 1u);
-        __syncthreads(); // all wavefronts are done with the previous block
+        for (uint32_t cb = it.wlo; cb <= it.whi; ++cb) {
+            // end of this tile's groups: requested before the refill so that the scalar
+            // load's latency hides behind it
+            const bool mine = cb >= it.mylo && cb <= it.myhi; // wave-uniform
+            const bool last = cb == it.whi;
+            const uint32_t g1 = tile_group[mine ? it.t0 + cb - it.mylo + 1 : 0u];
+            if (last && tid == 0)
+                s_next = atomicAdd(queue, 1u);
+            __syncthreads(); // all wavefronts are done with the previous block
 #ifdef BITGNN_PROFILE
-        { const long long t = BLK_PROF_T(); p_comp += t - p_t0; p_t0 = t; }
+            { const long long t = BLK_PROF_T(); p_comp += t - p_t0; p_t0 = t; }
 #endif
-        const uint32_t base = cb * cbn;
-        const uint32_t rows = n - base < cbn ? n - base : cbn;
-        // cbn <= 8192: at most 8 rows per thread, in two batches of 4 loads in flight
+            if (last) { // the drawn number is visible now: first descriptor of the next item
+                nx = s_next;
+                nw = wg_item[nx < n_items ? nx : n_items - 1];
+            }
+            const uint32_t base = cb * cbn;
+            const uint32_t rows = n - base < cbn ? n - base : cbn;
+            // cbn <= 8192: at most 8 rows per thread, in two batches of 4 loads in flight
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const uint32_t i0 = tid + (half * 4 + 0) * kBlkThreads;
-            const uint32_t i1 = tid + (half * 4 + 1) * kBlkThreads;
-            const uint32_t i2 = tid + (half * 4 + 2) * kBlkThreads;
-            const uint32_t i3 = tid + (half * 4 + 3) * kBlkThreads;
-            const uint4 st0 = hperm[base + (i0 < rows ? i0 : 0u)];
-            const uint4 st1 = hperm[base + (i1 < rows ? i1 : 0u)];
-            const uint4 st2 = hperm[base + (i2 < rows ? i2 : 0u)];
-            const uint4 st3 = hperm[base + (i3 < rows ? i3 : 0u)];
-            if (i0 < rows)
-                hblk[i0] = st0;
-            if (i1 < rows)
-                hblk[i1] = st1;
-            if (i2 < rows)
-                hblk[i2] = st2;
-            if (i3 < rows)
-                hblk[i3] = st3;
-        }
-        __syncthreads();
+            for (int half = 0; half < 2; ++half) {
+                const uint32_t i0 = tid + (half * 4 + 0) * kBlkThreads;
+                const uint32_t i1 = tid + (half * 4 + 1) * kBlkThreads;
+                const uint32_t i2 = tid + (half * 4 + 2) * kBlkThreads;
+                const uint32_t i3 = tid + (half * 4 + 3) * kBlkThreads;
+                const uint4 st0 = hperm[base + (i0 < rows ? i0 : 0u)];
+                const uint4 st1 = hperm[base + (i1 < rows ? i1 : 0u)];
+                const uint4 st2 = hperm[base + (i2 < rows ? i2 : 0u)];
+                const uint4 st3 = hperm[base + (i3 < rows ? i3 : 0u)];
+                if (i0 < rows)
+                    hblk[i0] = st0;
+                if (i1 < rows)
+                    hblk[i1] = st1;
+                if (i2 < rows)
+                    hblk[i2] = st2;
+                if (i3 < rows)
+                    hblk[i3] = st3;
+            }
+            __syncthreads();
 #ifdef BITGNN_PROFILE
-        { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
+            { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
 #endif
-        if (mine) {
-            for (; g < g1; ++g) {
-                // Unpack the ids first and pin them in registers: after that
-                // `nxt` is dead, the next request reuses its registers without a copy, and
-                // the wait for it moves to the top of the next iteration.
-                uint32_t id[kGroupSteps / 8][8];
+            if (last) { // second descriptor of the next item
+                nslice = nw.x * kSlicesPerWg + wave;
+                nhas = nslice < S;
+                nd = sl_desc[nhas ? nslice : 0u];
+            }
+            if (mine) {
+                for (; g < g1; ++g) {
+                    // Unpack the ids first and pin them in registers: after that
+                    // `nxt` is dead, the next request reuses its registers without a copy,
+                    // and the wait for it moves to the top of the next iteration.
+                    uint32_t id[kGroupSteps / 8][8];
 #pragma unroll
-                for (int j = 0; j < kGroupSteps / 2; ++j) {
-                    id[j / 4][2 * (j % 4)] = nxt.w[j] & 0xFFFFu;
-                    id[j / 4][2 * (j % 4) + 1] = nxt.w[j] >> 16;
-                }
+                    for (int j = 0; j < kGroupSteps / 2; ++j) {
+                        id[j / 4][2 * (j % 4)] = nxt.w[j] & 0xFFFFu;
+                        id[j / 4][2 * (j % 4) + 1] = nxt.w[j] >> 16;
+                    }
 #pragma unroll
-                for (int j = 0; j < kGroupSteps; ++j)
-                    asm volatile("" : "+v"(id[j / 8][j % 8]) : : "memory");
-                nxt = blk_load_ids(idx, g + 1, lane);
+                    for (int j = 0; j < kGroupSteps; ++j)
+                        asm volatile("" : "+v"(id[j / 8][j % 8]) : : "memory");
+                    nxt = blk_load_ids(idx, g + 1, lane);
 #pragma unroll
-                for (int j = 0; j < kGroupSteps / 8; ++j) {
-                    blk_consume<PP>(id[j], hblk, acc, pend, blk);
-                    ++blk;
+                    for (int j = 0; j < kGroupSteps / 8; ++j) {
+                        blk_consume<PP>(id[j], hblk, acc, pend, blk);
+                        ++blk;
+                    }
                 }
             }
         }
-    }
+        // first ids of the next item (the old `nxt` is one group past this item's stream)
+        const blk_item nit = blk_item_of(nw, nd, nslice, nhas);
+        nxt = blk_load_ids(idx, nit.g, lane);
 
 #ifdef BITGNN_PROFILE
-    __syncthreads();
-    if (tid == 0 && g_blk_prof) {
-        const long long t = clock64();
-        p_comp += t - p_t0;
-        unsigned long long *o = g_blk_prof + 8ull * cur;
-        o[0] = p_start; o[1] = t; o[2] = p_fill; o[3] = p_comp;
-        o[4] = p_wall0; o[5] = wall_clock64(); o[6] = __smid();
-        o[7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)); /* XCC_ID */
-    }
-#endif
-    // fold the parked carries: planes become an ordinary binary number
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        uint32_t carry = 0;
-#pragma unroll
-        for (int p = kPendLow; p < PP; ++p) {
-            const uint32_t pd =
-                (p < kPendTop && ((blk >> (p - kPendLow)) & 1u)) ? pend[p][q] : 0u;
-            uint32_t nc;
-            csa(acc[p][q], pd, carry, nc);
-            carry = nc;
+        __syncthreads();
+        if (tid == 0 && g_blk_prof) {
+            const long long t = clock64();
+            p_comp += t - p_t0;
+            unsigned long long *o = g_blk_prof + 8ull * cur;
+            o[0] = p_start; o[1] = t; o[2] = p_fill; o[3] = p_comp;
+            o[4] = p_wall0; o[5] = wall_clock64(); o[6] = __smid();
+            o[7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)); /* XCC_ID */
         }
-    }
-    // partial planes are filed under the part id, so that the merge reads the parts of a
-    // row, and of consecutive rows, back to back
-    const uint32_t pos = slice * 64 + lane;
-    if (has && pos < V) {
-        const uint32_t vid = part_vid[pos];
+#endif
+        // fold the parked carries: planes become an ordinary binary number
 #pragma unroll
-        for (int p = 0; p < PP; ++p)
-            partial[(uint64_t)vid * PP + p] =
-                make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
+        for (int q = 0; q < 4; ++q) {
+            uint32_t carry = 0;
+#pragma unroll
+            for (int p = kPendLow; p < PP; ++p) {
+                const uint32_t pd =
+                    (p < kPendTop && ((blk >> (p - kPendLow)) & 1u)) ? pend[p][q] : 0u;
+                uint32_t nc;
+                csa(acc[p][q], pd, carry, nc);
+                carry = nc;
+            }
+        }
+        // partial planes are filed under the part id, so that the merge reads the parts of
+        // a row, and of consecutive rows, back to back
+        if (writes) {
+#pragma unroll
+            for (int p = 0; p < PP; ++p)
+                partial[(uint64_t)vid * PP + p] =
+                    make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
+        }
+        cur = nx; // read behind the first barrier of the last block: uniform
+        if (cur >= n_items)
+            break;
+        it = nit;
     }
-    cur = s_next; // written before the barriers of the item's last block
-  }
 }
 
 // 4 lanes per node (one per 32-channel word of the window): sum the node's parts.
