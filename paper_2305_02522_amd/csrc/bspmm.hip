@@ -568,6 +568,44 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     }
 }
 
+// Adds the partial planes of the parts [v0, v1) of one node (word q) into acc.  Two parts
+// are requested per turn (the second address is clamped, so no load is conditional):
+// most nodes have at most a few parts, and the loads of a turn travel together.
+template <int P, int PP>
+__device__ __forceinline__ void add_parts(uint32_t (&acc)[P], const uint32_t *__restrict__ partial32,
+                                          uint32_t v0, uint32_t v1, int q)
+{
+    constexpr int kAdd = P < PP ? P : PP; // planes a part can fill
+    for (uint32_t v = v0; v < v1; v += 2) {
+        const bool two = v + 1 < v1; // lane-varying: handled by masking, not by branching
+        const uint32_t *pa = partial32 + ((uint64_t)v * PP) * 4 + q;
+        const uint32_t *pb = partial32 + ((uint64_t)(two ? v + 1 : v) * PP) * 4 + q;
+        uint32_t a[kAdd], b[kAdd];
+#pragma unroll
+        for (int p = 0; p < kAdd; ++p) {
+            a[p] = pa[p * 4];
+            b[p] = pb[p * 4];
+        }
+        const uint32_t keep = two ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) { // acc += a, then acc += b (or 0)
+            uint32_t carry = 0;
+#pragma unroll
+            for (int p = 0; p < kAdd; ++p) {
+                uint32_t nc;
+                csa(acc[p], h == 0 ? a[p] : (b[p] & keep), carry, nc);
+                carry = nc;
+            }
+#pragma unroll
+            for (int p = kAdd; p < P; ++p) {
+                const uint32_t nc = acc[p] & carry;
+                acc[p] ^= carry;
+                carry = nc;
+            }
+        }
+    }
+}
+
 // 4 lanes per node (one per 32-channel word of the window): sum the node's parts.
 template <int P, int EPI, int PP>
 __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
@@ -588,23 +626,7 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
 #pragma unroll
     for (int p = 0; p < P; ++p)
         acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((d & 1u) * P + p) * W32 + w] : 0u;
-    const uint32_t v1 = row_vptr[slot + 1];
-    for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
-        const uint32_t *pp = partial32 + ((uint64_t)v * PP) * 4 + q;
-        uint32_t carry = 0;
-#pragma unroll
-        for (int p = 0; p < PP; ++p) {
-            uint32_t nc;
-            csa(acc[p], pp[p * 4], carry, nc);
-            carry = nc;
-        }
-#pragma unroll
-        for (int p = PP; p < P; ++p) {
-            const uint32_t nc = acc[p] & carry;
-            acc[p] ^= carry;
-            carry = nc;
-        }
-    }
+    add_parts<P, PP>(acc, partial32, row_vptr[slot], row_vptr[slot + 1], q);
     bspmm_epilogue<P, EPI>(acc, d, row, w, W32, C, out, out_stride);
 }
 
@@ -679,14 +701,33 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     float *__restrict__ out, int64_t ldo)
 {
     constexpr int P = 7 * NB;
-    constexpr int kAdd = P < PP ? P : PP; // planes a part can fill
-    __shared__ uint32_t s_planes[kProjWaves][16][4][P + 1];
-    __shared__ float s_out[kProjWaves][16][kProjTiles * 16 + 1];
+    // per wavefront: first the merged planes [node][word][plane], later (same memory, the
+    // planes are consumed by then and the region is private to the wavefront) the logits
+    // [node][class] on their way out
+    constexpr int kPlaneWords = 16 * 4 * (P + 1), kOutWords = 16 * (kProjTiles * 16 + 1);
+    __shared__ uint32_t s_buf[kProjWaves][kPlaneWords > kOutWords ? kPlaneWords : kOutWords];
     __shared__ int32_t s_deg[kProjWaves][16];
     __shared__ uint32_t s_row[kProjWaves][16];
+    __shared__ int32_t s_wsum[kProjTiles * 16];
+    __shared__ float s_alpha[kProjTiles * 16];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const uint32_t slot0 = (blockIdx.x * kProjWaves + wave) * 16;
+    // per-class constants and weight operands of the first 64 classes: requested before the
+    // parts are merged, so that their latency hides behind that
+    if (threadIdx.x < kProjTiles * 16) {
+        const int c = threadIdx.x;
+        s_wsum[c] = c < M ? wsum[c] : 0;
+        s_alpha[c] = c < M ? alpha[c] : 0.0f;
+    }
+    long aop[kProjTiles][4];
+#pragma unroll
+    for (int t = 0; t < kProjTiles; ++t)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int row = t * 16 < M ? t * 16 + (lane & 15) : (lane & 15); // rows padded to 16
+            aop[t][w] = *(const long *)(w8 + (int64_t)row * 128 + 8 * (lane >> 4) + 32 * w);
+        }
 
     // --- merge the parts of 16 nodes (lane = node * 4 + word)
     {
@@ -699,28 +740,11 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
 #pragma unroll
         for (int p = 0; p < P; ++p)
             acc[p] = 0u;
-        if (live && q < W32) {
-            const uint32_t v1 = row_vptr[slot + 1];
-            for (uint32_t v = row_vptr[slot]; v < v1; ++v) {
-                const uint32_t *pp = partial32 + ((uint64_t)v * PP) * 4 + q;
-                uint32_t carry = 0;
-#pragma unroll
-                for (int p = 0; p < kAdd; ++p) {
-                    uint32_t nc;
-                    csa(acc[p], pp[p * 4], carry, nc);
-                    carry = nc;
-                }
-#pragma unroll
-                for (int p = kAdd; p < P; ++p) {
-                    const uint32_t nc = acc[p] & carry;
-                    acc[p] ^= carry;
-                    carry = nc;
-                }
-            }
-        }
+        if (live && q < W32)
+            add_parts<P, PP>(acc, partial32, row_vptr[slot], row_vptr[slot + 1], q);
 #pragma unroll
         for (int p = 0; p < P; ++p)
-            s_planes[wave][node][q][p] = acc[p];
+            s_buf[wave][(node * 4 + q) * (P + 1) + p] = acc[p];
         if (q == 0) {
             s_deg[wave][node] = live ? deg[row] : 0;
             s_row[wave][node] = live ? row : 0xFFFFFFFFu;
@@ -737,7 +761,7 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
         for (int w = 0; w < 4; ++w)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const uint32_t *pl = &s_planes[wave][nd][w][7 * b];
+                const uint32_t *pl = &s_buf[wave][(nd * 4 + w) * (P + 1) + 7 * b];
                 // byte g of planes 7b .. 7b+6: rows of an 8x8 bit matrix (row 7 is zero)
                 const uint32_t h01 = __builtin_amdgcn_perm(pl[1], pl[0], sel01);
                 const uint32_t h23 = __builtin_amdgcn_perm(pl[3], pl[2], sel01);
@@ -753,6 +777,22 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
 
     // --- contraction with the class weights, 64 classes per pass
     for (int c0 = 0; c0 < M; c0 += kProjTiles * 16) {
+        if (c0 > 0) { // later passes: constants and operands of these 64 classes
+            __syncthreads(); // the previous pass has read s_wsum / s_alpha / s_out
+            if (threadIdx.x < kProjTiles * 16) {
+                const int c = c0 + threadIdx.x;
+                s_wsum[threadIdx.x] = c < M ? wsum[c] : 0;
+                s_alpha[threadIdx.x] = c < M ? alpha[c] : 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < kProjTiles; ++t)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const int row = c0 + t * 16 < M ? c0 + t * 16 + nd : nd;
+                    aop[t][w] = *(const long *)(w8 + (int64_t)row * 128 + 8 * g + 32 * w);
+                }
+            __syncthreads();
+        }
         v4i acc[kProjTiles][NB];
 #pragma unroll
         for (int t = 0; t < kProjTiles; ++t)
@@ -761,42 +801,38 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
                 acc[t][b] = (v4i){0, 0, 0, 0};
 #pragma unroll
         for (int t = 0; t < kProjTiles; ++t) {
-            if (c0 + t * 16 < M) { // wave-uniform; w8 rows are padded to a multiple of 16
-                const int8_t *wr = w8 + (int64_t)(c0 + t * 16 + nd) * 128 + 8 * g;
+            if (c0 + t * 16 < M) { // wave-uniform
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     if (w < W32) {
-                        const long a = *(const long *)(wr + 32 * w);
 #pragma unroll
                         for (int b = 0; b < NB; ++b)
-                            acc[t][b] = __builtin_amdgcn_mfma_i32_16x16x32_i8(a, bop[w][b],
-                                                                              acc[t][b], 0, 0, 0);
+                            acc[t][b] = __builtin_amdgcn_mfma_i32_16x16x32_i8(
+                                aop[t][w], bop[w][b], acc[t][b], 0, 0, 0);
                     }
                 }
             }
         }
-        __syncthreads(); // the staging tile of the previous pass has been written out
 #pragma unroll
         for (int t = 0; t < kProjTiles; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int cl = t * 16 + 4 * g + j;
-                const int c = c0 + cl;
                 int32_t val = 0;
 #pragma unroll
                 for (int b = NB - 1; b >= 0; --b)
                     val = (val << 7) + acc[t][b][j];
-                float y = 0.0f;
-                if (c < M)
-                    y = alpha[c] * (float)(2 * val - d_nd * wsum[c]);
-                s_out[wave][nd][cl] = y;
+                // classes beyond M have alpha 0 and weight rows 0
+                s_buf[wave][nd * (kProjTiles * 16 + 1) + cl] =
+                    __float_as_uint(s_alpha[cl] * (float)(2 * val - d_nd * s_wsum[cl]));
             }
         __syncthreads();
         const int ncls = M - c0 < kProjTiles * 16 ? M - c0 : kProjTiles * 16;
         for (int node = 0; node < 16; ++node) {
             const uint32_t row = s_row[wave][node];
             if (row != 0xFFFFFFFFu && lane < ncls)
-                out[(int64_t)row * ldo + c0 + lane] = s_out[wave][node][lane];
+                out[(int64_t)row * ldo + c0 + lane] =
+                    __uint_as_float(s_buf[wave][node * (kProjTiles * 16 + 1) + lane]);
         }
     }
 }
