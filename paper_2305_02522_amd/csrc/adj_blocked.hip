@@ -435,6 +435,11 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     constexpr uint64_t kGroupIds = 64ull * kGroupSteps;
     if (((uint64_t)G + 1) * kGroupIds * 2 >= (1ull << 32)) // the kernel uses 32-bit byte offsets
         return BITGNN_OK;
+    // Many column blocks with few neighbours each pad the tiles heavily: beyond 6 stored
+    // ids per non-zero the plain CSR kernel is the better choice (a threshold of 0 stored
+    // non-zeros per node forces the blocked form whatever the padding).
+    if (ctx->min_avg_degree > 0 && (uint64_t)G * kGroupIds > 6ull * nnz)
+        return BITGNN_OK;
 
     DevBuf idx16;
     BG_HIP(ctx, idx16.alloc(((size_t)G + 1) * kGroupIds * 2));
@@ -473,6 +478,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     b->cbn = cbn;
     b->ncb = (int32_t)ncb;
     b->part_len = part_len;
+    b->forced = ctx->min_avg_degree == 0;
     b->n_vrows = V;
     b->n_slices = S;
     b->n_wgs = W;

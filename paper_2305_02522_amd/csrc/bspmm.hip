@@ -647,29 +647,30 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
 //   result: lane = node + 16 * g     holds classes 16 tile + 4 g + (0..3)
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-// +-1 bytes of the class weights, rows padded to 128 channels and to a multiple of 16
-// classes, plus the column sums; written per call into the workspace (a few KB).
+// +-1 bytes of the class weights per window of 128 channels (0 beyond K or M), class rows
+// padded to a multiple of 16, plus the column sums of every window; written per call
+// into the workspace (a few KB).  Layout: w8[(win * Mpad + c) * 128 + k], wsum[win * Mpad + c].
 __global__ void project_weights_kernel(const uint32_t *__restrict__ w32, int64_t w_stride32,
                                        int32_t K, int32_t M, int32_t Mpad,
                                        int8_t *__restrict__ w8, int32_t *__restrict__ wsum)
 {
-    const int c = blockIdx.x, k = threadIdx.x; // 128 threads
+    const int c = blockIdx.x, win = blockIdx.y, t = threadIdx.x; // 128 threads
+    const int k = win * 128 + t;
     int v = 0;
     if (c < M && k < K)
         v = ((w32[(int64_t)c * w_stride32 + (k >> 5)] >> (k & 31)) & 1u) ? 1 : -1;
-    w8[c * 128 + k] = (int8_t)v;
+    w8[((int64_t)win * Mpad + c) * 128 + t] = (int8_t)v;
     // column sum: two wavefronts, combined through LDS
     __shared__ int part[2];
     int sum = v;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1)
         sum += __shfl_xor(sum, d, 64);
-    if ((k & 63) == 0)
-        part[k >> 6] = sum;
+    if ((t & 63) == 0)
+        part[t >> 6] = sum;
     __syncthreads();
-    if (k == 0)
-        wsum[c] = part[0] + part[1];
-    (void)Mpad;
+    if (t == 0)
+        wsum[win * Mpad + c] = part[0] + part[1];
 }
 
 // 8x8 bit transpose of the 64-bit matrix (hi:lo), row r = byte r: three delta swaps.
@@ -698,8 +699,12 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     const int32_t *__restrict__ order,
     const int32_t *__restrict__ deg, uint32_t n, int32_t W32, const int8_t *__restrict__ w8,
     const int32_t *__restrict__ wsum, int32_t M, const float *__restrict__ alpha,
-    float *__restrict__ out, int64_t ldo)
+    float *__restrict__ out, int64_t ldo, int32_t *__restrict__ ysum, bool has_prev,
+    bool is_last)
 {
+    // K > 128 comes in windows of 128 channels, one call each: the integer sums of the
+    // windows are chained through ysum[n][M] (has_prev: add it; !is_last: store there),
+    // the last call scales and writes the logits.
     constexpr int P = 7 * NB;
     // per wavefront: first the merged planes [node][word][plane], later (same memory, the
     // planes are consumed by then and the region is private to the wavefront) the logits
@@ -822,17 +827,22 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
 #pragma unroll
                 for (int b = NB - 1; b >= 0; --b)
                     val = (val << 7) + acc[t][b][j];
-                // classes beyond M have alpha 0 and weight rows 0
                 s_buf[wave][nd * (kProjTiles * 16 + 1) + cl] =
-                    __float_as_uint(s_alpha[cl] * (float)(2 * val - d_nd * s_wsum[cl]));
+                    (uint32_t)(2 * val - d_nd * s_wsum[cl]);
             }
         __syncthreads();
         const int ncls = M - c0 < kProjTiles * 16 ? M - c0 : kProjTiles * 16;
         for (int node = 0; node < 16; ++node) {
             const uint32_t row = s_row[wave][node];
-            if (row != 0xFFFFFFFFu && lane < ncls)
-                out[(int64_t)row * ldo + c0 + lane] =
-                    __uint_as_float(s_buf[wave][node * (kProjTiles * 16 + 1) + lane]);
+            if (row != 0xFFFFFFFFu && lane < ncls) {
+                int32_t y = (int32_t)s_buf[wave][node * (kProjTiles * 16 + 1) + lane];
+                if (has_prev)
+                    y += ysum[(int64_t)row * M + c0 + lane];
+                if (is_last)
+                    out[(int64_t)row * ldo + c0 + lane] = s_alpha[lane] * (float)y;
+                else
+                    ysum[(int64_t)row * M + c0 + lane] = y;
+            }
         }
     }
 }
@@ -1003,67 +1013,96 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     return BITGNN_OK;
 }
 
-// logits = alpha * ((A_hat v) W) through the blocked form (K <= 128).
+// logits = alpha * ((A_hat v) W) through the blocked form, 128 channels of v per pass.
 int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
                                   const uint64_t *hbits, int32_t K, int64_t h_stride,
                                   const uint64_t *wbits, int32_t M, int64_t w_stride,
-                                  const float *alpha, float *logits, int64_t ldo)
+                                  const float *alpha, int32_t *ysum, float *logits, int64_t ldo)
 {
     const bitgnn_blocked *b = adj->blk;
     const int32_t W32 = (K + 31) / 32;
+    const int nwin = (W32 + 3) / 4;
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
     const size_t part_bytes =
         ((size_t)b->n_vrows * part_planes_for(b) * 16 + 255) & ~(size_t)255;
     const int32_t Mpad = (M + 15) / 16 * 16;
-    const size_t w8_bytes = (size_t)Mpad * 128;
-    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)Mpad * 4);
+    const size_t w8_bytes = (size_t)nwin * Mpad * 128;
+    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)nwin * Mpad * 4);
     if (rc != BITGNN_OK)
         return rc;
     uint4 *hperm = (uint4 *)ctx->ws;
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
     int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
     int32_t *wsum = (int32_t *)(w8 + w8_bytes);
-    blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
-        (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, 0, W32, hperm,
-        ctx->queue);
-    rc = launch_blk(ctx, s, adj, hperm, partial);
-    if (rc != BITGNN_OK)
-        return rc;
-    project_weights_kernel<<<Mpad, 128, 0, s>>>((const uint32_t *)wbits, w_stride * 2, K, M, Mpad,
-                                                w8, wsum);
+    project_weights_kernel<<<dim3(Mpad, nwin), 128, 0, s>>>((const uint32_t *)wbits, w_stride * 2,
+                                                            K, M, Mpad, w8, wsum);
     BG_LAUNCH_CHECK(ctx, "project_weights");
     const unsigned grid = (unsigned)((adj->n + kProjWaves * 16 - 1) / (kProjWaves * 16));
     // digits of 7 bits: max_degree < 2^(7 NB)
     int NB = 1;
     while ((1ll << (7 * NB)) <= adj->max_degree)
         ++NB;
+    for (int win = 0; win < nwin; ++win) {
+        blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
+            (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32,
+            hperm, ctx->queue);
+        rc = launch_blk(ctx, s, adj, hperm, partial);
+        if (rc != BITGNN_OK)
+            return rc;
+        const int32_t w32w = W32 - win * 4 < 4 ? W32 - win * 4 : 4;
+        const int8_t *w8w = w8 + (size_t)win * Mpad * 128;
+        const int32_t *wsumw = wsum + (size_t)win * Mpad;
+        const bool has_prev = win > 0, is_last = win == nwin - 1;
 #define BG_PROJECT(NBV)                                                                           \
     do {                                                                                          \
         if (part_planes_for(b) == 8)                                                              \
             bspmm_merge_project_kernel<NBV, 8><<<grid, kProjWaves * 64, 0, s>>>(                  \
                 (const uint32_t *)partial, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n,   \
-                W32, w8, wsum, M, alpha, logits, ldo);                                            \
+                w32w, w8w, wsumw, M, alpha, logits, ldo, ysum, has_prev, is_last);                \
         else                                                                                      \
             bspmm_merge_project_kernel<NBV, 10><<<grid, kProjWaves * 64, 0, s>>>(                 \
                 (const uint32_t *)partial, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n,   \
-                W32, w8, wsum, M, alpha, logits, ldo);                                            \
+                w32w, w8w, wsumw, M, alpha, logits, ldo, ysum, has_prev, is_last);                \
     } while (0)
-    switch (NB) {
-    case 1: BG_PROJECT(1); break;
-    case 2: BG_PROJECT(2); break;
-    case 3: BG_PROJECT(3); break;
-    default: BG_PROJECT(4); break;
-    }
+        switch (NB) {
+        case 1: BG_PROJECT(1); break;
+        case 2: BG_PROJECT(2); break;
+        case 3: BG_PROJECT(3); break;
+        default: BG_PROJECT(4); break;
+        }
 #undef BG_PROJECT
-    BG_LAUNCH_CHECK(ctx, "bspmm_merge_project");
+        BG_LAUNCH_CHECK(ctx, "bspmm_merge_project");
+    }
     return BITGNN_OK;
+}
+
+// Rough time models (microseconds, fitted on MI355X) of the two aggregation paths.  The
+// CSR kernel is bound by its gather traffic or by the serial walk of the longest row;
+// the blocked kernel by its id stream or, on small graphs, by the chain of LDS refills a
+// workgroup walks through, and it pays that once per 128-channel pass.
+bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
+                       double chain_us_per_nnz)
+{
+    const bitgnn_blocked *b = adj->blk;
+    if (!b)
+        return false;
+    if (b->forced)
+        return true;
+    const double csr_traffic = (double)adj->nnz * (double)bytes_per_nnz / 1.5e6;
+    const double csr_chain = (double)adj->max_degree * chain_us_per_nnz;
+    const double csr = (csr_traffic > csr_chain ? csr_traffic : csr_chain) + 10.0;
+    const double stream = (double)b->n_groups * 64 * kGroupSteps / 1.3e6;
+    const double rounds = (double)((b->n_wgs + 255) / 256);
+    const double walk = rounds * (double)b->ncb * 3.0;
+    const double blk = passes * ((stream > walk ? stream : walk) + 30.0);
+    return blk < csr;
 }
 
 int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint64_t *hbits,
                     int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
                     int64_t out_stride)
 {
-    if (adj->blk)
+    if (bg_prefer_blocked(adj, (C + 127) / 128, 4 * (int64_t)((C + 31) / 32), 0.06))
         return bg_launch_bspmm_blocked(ctx, s, adj, hbits, C, h_stride, epilogue, T, out,
                                        out_stride);
     const int32_t W32 = (C + 31) / 32;

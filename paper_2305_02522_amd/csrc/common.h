@@ -66,6 +66,7 @@ struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
     int32_t ncb;            // column blocks
     int32_t part_len;       // longest row part (sets the planes of the partial counters)
+    int32_t forced;         // built with a density threshold of 0: always preferred
     uint32_t n_vrows;       // V: row parts ("virtual rows")
     uint32_t n_slices;      // ceil(V / 64)
     uint32_t n_wgs;         // ceil(slices / kSlicesPerWg)
@@ -159,10 +160,14 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
                             const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
                             const int32_t *T, void *out, int64_t out_stride);
 int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes);
+// Whether the blocked form is expected to beat the CSR kernel for rows of `bytes_per_nnz`
+// gathered bytes per non-zero, handled in `passes` passes of the blocked kernel.
+bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
+                       double chain_us_per_nnz);
 int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
                                   const uint64_t *hbits, int32_t K, int64_t h_stride,
                                   const uint64_t *wbits, int32_t M, int64_t w_stride,
-                                  const float *alpha, float *logits, int64_t ldo);
+                                  const float *alpha, int32_t *ysum, float *logits, int64_t ldo);
 
 int bg_check_bgemm_f32(bitgnn_ctx *ctx, const float *x, int64_t n, int32_t K, int64_t ldx,
                        const float *tau, const uint64_t *wbits, int32_t M, int64_t w_stride,

@@ -16,7 +16,7 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
     ctx->device = device;
     ctx->cb_nodes = 8192;
     ctx->part_len = 255;
-    ctx->min_avg_degree = 32;
+    ctx->min_avg_degree = 8;
     if (device >= 0) {
         int count = 0;
         hipError_t e = hipGetDeviceCount(&count);

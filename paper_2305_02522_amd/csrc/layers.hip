@@ -85,12 +85,14 @@ extern "C" int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_
     BG_NEED_DEVICE(ctx);
     hipStream_t s = (hipStream_t)stream;
     // No non-linearity sits between the two products, so A_hat (x W) = (A_hat x) W in
-    // exact integers.  With the blocked form and K <= 128 the aggregation runs first, on
-    // 1-bit rows staged in LDS, and the class projection is fused into its merge step;
-    // otherwise the int32 rows of x W are aggregated directly.
-    if (adj->blk && kwords <= 2 && K <= 128 && (int64_t)K * adj->max_degree < (1ll << 29))
+    // exact integers.  With the blocked form the aggregation runs first, on 1-bit rows
+    // staged in LDS (128 channels per pass), and the class projection is fused into its
+    // merge step (tmp_i32 chains the integer sums of the passes when K > 128); otherwise
+    // the int32 rows of x W are aggregated directly.
+    if ((int64_t)K * adj->max_degree < (1ll << 29) &&
+        bg_prefer_blocked(adj, (K + 127) / 128, 4 * (int64_t)M, 0.25))
         return bg_launch_agg_project_blocked(ctx, s, adj, xbits, K, x_stride, wbits, M, w_stride,
-                                             alpha, logits, ldo);
+                                             alpha, tmp_i32, logits, ldo);
     rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
                          BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_i32, M);
     if (rc != BITGNN_OK)

@@ -26,7 +26,7 @@ def ctx(B):
     c.close()
 
 
-TUNINGS = {"default": (8192, 255, 32), "csr-only": (8192, 255, 1 << 30),
+TUNINGS = {"default": (8192, 255, 8), "csr-only": (8192, 255, 1 << 30),
            "blocked-small": (128, 16, 0), "blocked-long-parts": (64, 1023, 0),
            "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0)}
 
@@ -373,7 +373,9 @@ def test_model_small(B, ctx, tuned, cfg, kw):
 
 
 @pytest.mark.parametrize("n,e,K,M", [(300, 4000, 7, 3), (2000, 90000, 64, 41),
-                                     (5000, 200000, 128, 41), (3000, 150000, 100, 130)])
+                                     (5000, 200000, 128, 41), (3000, 150000, 100, 130),
+                                     (1500, 40000, 129, 7), (2000, 60000, 300, 41),
+                                     (1000, 30000, 512, 70)])
 def test_gcn_out_layer_both_orders(B, ctx, tuned, n, e, K, M):
     """The output layer may aggregate first and transform second: same integers."""
     adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + K + M, hubs=1)
