@@ -356,6 +356,9 @@ int bg_launch_bgemm(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64
 {
     if (n == 0)
         return BITGNN_OK;
+    if (bg_bgemm_mfma_applies(ctx, n, kwords, M))
+        return bg_launch_bgemm_mfma(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                                    epilogue, T, alpha, out, out_stride);
     const int64_t gx = (n + kWaves * kRows - 1) / (kWaves * kRows);
     BG_REQUIRE(ctx, gx < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bgemm: n too large");
     dim3 grid((unsigned)gx, (unsigned)((M + 63) / 64));

@@ -1,0 +1,314 @@
+// BMM on the matrix cores (Section 2.2: c = n - 2 popc(a xor b); the paper runs it on
+// 1-bit tensor cores, which CDNA4 does not have).  The product is a dense contraction, so
+// the bits are widened to 0/1 bytes on the fly and fed to v_mfma_i32_16x16x64_i8:
+//   D[i][c] = sum_k x_ik w_kc            (x, w in {0,1})
+//   popc(x_i xor w_c) = px_i + pw_c - 2 D[i][c]
+//   Z[i][c] = K - 2 px_i - 2 pw_c + 4 D[i][c]
+// with px, pw the popcounts of the stored rows (pad bits are zero in both operands).
+//
+// gfx950 mapping
+//  - the weights, widened once per call to bytes (row stride K' + 16 so that the 16-byte
+//    operand reads of 16 columns fall into different LDS bank groups), stay in LDS for the
+//    whole life of a persistent workgroup (hence the limit M' (K' + 16) <= 144 KB);
+//  - a wavefront owns 32 rows (two A operands, widened from their packed words with
+//    three VALU ops per four bytes) and walks column groups of 128: 16 accumulators of
+//    16x16, every B operand read from LDS feeds two MFMAs;
+//  - the epilogue works on the accumulator layout (lane = column, 4 rows): integers and
+//    logits are stored as 64-byte row segments, thresholded bits are gathered from wave
+//    votes into whole 64-bit words.
+// Against the VALU kernel (2 lane-ops per 32 bit-MACs: 629 T bit-MAC/s at peak, ~310
+// reached) the int8 MFMA peak is 2,500 T MAC/s; this kernel reaches ~590 on 2.4 M x 512 x 256
+// (widening and the bit-packing epilogue share the issue slots with the MFMAs).  It is
+// chosen when the weights fit in LDS and there are enough rows to repay the set-up.
+#include "common.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kMfWaves = 8;            // wavefronts per workgroup
+constexpr int kMfRows = 32;            // rows per wavefront (two 16-row operands)
+constexpr int kMfPanel = kMfWaves * kMfRows;
+constexpr int kMfGroup = 8;            // column tiles of 16 per pass (128 columns)
+constexpr int kMfColGroups = 2;        // column groups whose per-lane constants stay in registers
+constexpr size_t kMfLdsLimit = 144 * 1024;
+
+// w8[c * ldw + k] = stored bit k of weight row c (0 beyond the kbits stored bits or M);
+// pw[c] = its popcount.  Every stored bit position counts, not only k < K: rows may hold
+// pad bits in the middle (concatenated segments), which are zero in both operands.
+__global__ __launch_bounds__(256) void bgemm_widen_w_kernel(const uint32_t *__restrict__ w32,
+                                                            int64_t w_stride32, int32_t kbits,
+                                                            int32_t M, int32_t ldw,
+                                                            uint8_t *__restrict__ w8,
+                                                            int32_t *__restrict__ pw)
+{
+    __shared__ int part[4];
+    const int c = blockIdx.x, t = threadIdx.x;
+    int cnt = 0;
+    for (int k = t; k < ldw; k += 256) {
+        int v = 0;
+        if (c < M && k < kbits)
+            v = (w32[(int64_t)c * w_stride32 + (k >> 5)] >> (k & 31)) & 1u;
+        w8[(int64_t)c * ldw + k] = (uint8_t)v;
+        cnt += v;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        cnt += __shfl_xor(cnt, d, 64);
+    if ((t & 63) == 0)
+        part[t >> 6] = cnt;
+    __syncthreads();
+    if (t == 0)
+        pw[c] = part[0] + part[1] + part[2] + part[3];
+}
+
+// 16 bits -> 16 bytes of 0/1 (one MFMA operand of a lane)
+__device__ __forceinline__ v4i widen16(uint32_t bits)
+{
+    v4i r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        r[i] = (int)((((bits >> (4 * i)) & 0xFu) * 0x00204081u) & 0x01010101u);
+    return r;
+}
+
+// KS = 64-bit words of a packed row held in registers (K <= 64 KS; 2, 4 or 8).
+template <int EPI, int KS>
+__global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
+    const uint64_t *__restrict__ xbits, int64_t n, int64_t x_stride, int32_t K, int32_t ksteps,
+    const uint4 *__restrict__ w8g, int32_t ldw, const int32_t *__restrict__ pw, int32_t M,
+    int32_t Mp, const int32_t *__restrict__ T, const float *__restrict__ alpha,
+    void *__restrict__ out, int64_t out_stride)
+{
+    extern __shared__ uint4 wl[]; // Mp rows of ldw bytes
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    for (int i = tid; i < Mp * (ldw / 16); i += kMfWaves * 64)
+        wl[i] = w8g[i];
+    __syncthreads(); // the only barrier: the weights are read-only from here on
+    const char *wbytes = (const char *)wl;
+    const int64_t last = n - 1;
+    // per-lane column constants of up to kMfColGroups x kMfGroup tiles, fixed for the run:
+    // THRESH: T - K + 2 pw (a column beyond M never passes); else K - 2 pw and the scale
+    int32_t colk[kMfColGroups][kMfGroup];
+    float colf[kMfColGroups][kMfGroup];
+#pragma unroll
+    for (int cgi = 0; cgi < kMfColGroups; ++cgi)
+#pragma unroll
+        for (int t = 0; t < kMfGroup; ++t) {
+            const int c = (cgi * kMfGroup + t) * 16 + r;
+            const bool c_ok = c < M;
+            const int pwc = c_ok ? pw[c] : 0;
+            if (EPI == BITGNN_EPI_THRESH_BITS)
+                colk[cgi][t] = c_ok ? T[c] - K + 2 * pwc : 0x7FFFFFFF;
+            else
+                colk[cgi][t] = K - 2 * pwc;
+            colf[cgi][t] = (EPI == BITGNN_EPI_SCALE_F32 && c_ok) ? alpha[c] : 0.0f;
+        }
+
+    // the packed words of the wavefront's two 16-row operands (clamped row and word index:
+    // no load is conditional, so all of them travel together)
+    auto load_rows = [&](int64_t panel, uint64_t (&wa)[KS], uint64_t (&wb)[KS]) {
+        const int64_t row0 = panel * kMfPanel + wave * kMfRows;
+        const int64_t ra = row0 + r < last ? row0 + r : last;
+        const int64_t rb = row0 + 16 + r < last ? row0 + 16 + r : last;
+        const uint64_t *xa = xbits + ra * x_stride, *xb = xbits + rb * x_stride;
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+            const int sc = u < ksteps ? u : ksteps - 1;
+            wa[u] = xa[sc];
+            wb[u] = xb[sc];
+        }
+    };
+
+    auto compute = [&](int64_t panel, const uint64_t (&wa)[KS], const uint64_t (&wb)[KS]) {
+        const int64_t row0 = panel * kMfPanel + wave * kMfRows;
+        if (row0 >= n)
+            return;
+        int pxa = 0, pxb = 0;
+#pragma unroll
+        for (int u = 0; u < KS; ++u)
+            if (u < ksteps) {
+                pxa += __popcll(wa[u]);
+                pxb += __popcll(wb[u]);
+            }
+#pragma unroll
+        for (int cg = 0; cg < kMfColGroups; ++cg) { // static index into the column constants
+            const int c0 = cg * kMfGroup * 16;
+            if (c0 >= Mp) // wave-uniform
+                continue;
+            const int ntile = (Mp - c0) / 16 < kMfGroup ? (Mp - c0) / 16 : kMfGroup;
+            v4i acc[2][kMfGroup];
+#pragma unroll
+            for (int t = 0; t < kMfGroup; ++t)
+                acc[0][t] = acc[1][t] = (v4i){0, 0, 0, 0};
+            const char *wcol = wbytes + (size_t)(c0 + r) * ldw + 16 * g;
+#pragma unroll
+            for (int u = 0; u < KS; ++u) {
+                if (u < ksteps) { // wave-uniform
+                    const v4i a0 = widen16((uint32_t)(wa[u] >> (16 * g)) & 0xFFFFu);
+                    const v4i a1 = widen16((uint32_t)(wb[u] >> (16 * g)) & 0xFFFFu);
+                    const char *wk = wcol + 64 * u;
+#pragma unroll
+                    for (int t = 0; t < kMfGroup; ++t) {
+                        if (t < ntile) { // wave-uniform
+                            const v4i b = *(const v4i *)(wk + (size_t)t * 16 * ldw);
+                            acc[0][t] =
+                                __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b, acc[0][t], 0, 0, 0);
+                            acc[1][t] =
+                                __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b, acc[1][t], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            // accumulator layout: lane = column (r), rows 4 g + j of the 16-row operand.
+            // Z = K - 2 px - 2 pw + 4 D: the column part (colk) is fixed per lane and tile.
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int px_mine = h == 0 ? pxa : pxb; // held by the lane whose r is the row
+                int px2[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    px2[j] = 2 * __shfl(px_mine, 4 * g + j, 64);
+                const int64_t rbase = row0 + 16 * h + 4 * g;
+                if (EPI == BITGNN_EPI_THRESH_BITS) {
+                    // bit = (4 D - 2 px >= T - K + 2 pw); lane w < 16 assembles the words of
+                    // row w = 4 g' + j': vote[t][j] bits 16 g' .. 16 g' + 15 are that row's
+                    // columns 16 t .. 16 t + 15
+                    const int gw = (lane >> 2) & 3, jw = lane & 3;
+                    const uint32_t sh = 16u * (gw & 1);
+                    uint32_t lo[kMfGroup / 4] = {}, hi[kMfGroup / 4] = {};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        uint32_t f[kMfGroup];
+#pragma unroll
+                        for (int t = 0; t < kMfGroup; ++t) {
+                            const uint64_t v = __ballot(4 * acc[h][t][j] - px2[j] >= colk[cg][t]);
+                            const uint32_t half = gw < 2 ? (uint32_t)v : (uint32_t)(v >> 32);
+                            f[t] = (half >> sh) & 0xFFFFu;
+                        }
+#pragma unroll
+                        for (int wi = 0; wi < kMfGroup / 4; ++wi) {
+                            const uint32_t l = f[4 * wi] | (f[4 * wi + 1] << 16);
+                            const uint32_t u = f[4 * wi + 2] | (f[4 * wi + 3] << 16);
+                            lo[wi] = jw == j ? l : lo[wi];
+                            hi[wi] = jw == j ? u : hi[wi];
+                        }
+                    }
+                    const int64_t row = row0 + 16 * h + lane;
+#pragma unroll
+                    for (int wi = 0; wi < kMfGroup / 4; ++wi) {
+                        const int wcolumn = c0 / 64 + wi;
+                        if (lane < 16 && row < n && wcolumn * 64 < M)
+                            ((uint64_t *)out)[row * out_stride + wcolumn] =
+                                ((uint64_t)hi[wi] << 32) | lo[wi];
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < kMfGroup; ++t) {
+                        const int c = c0 + 16 * t + r;
+                        const bool c_ok = t < ntile && c < M;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            // colk holds K - 2 pw here
+                            const int32_t z = 4 * acc[h][t][j] - px2[j] + colk[cg][t];
+                            if (c_ok && rbase + j < n) {
+                                if (EPI == BITGNN_EPI_RAW_I32)
+                                    ((int32_t *)out)[(rbase + j) * out_stride + c] = z;
+                                else
+                                    ((float *)out)[(rbase + j) * out_stride + c] =
+                                        colf[cg][t] * (float)z;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    // two register sets: the rows of the next panel are requested before the current
+    // panel is computed
+    uint64_t a0[KS], a1[KS], b0[KS], b1[KS];
+    int64_t panel = blockIdx.x;
+    const int64_t step = gridDim.x;
+    load_rows(panel, a0, a1);
+    for (;;) {
+        load_rows(panel + step, b0, b1);
+        compute(panel, a0, a1);
+        panel += step;
+        if (panel * kMfPanel >= n) // uniform over the workgroup
+            break;
+        load_rows(panel + step, a0, a1);
+        compute(panel, b0, b1);
+        panel += step;
+        if (panel * kMfPanel >= n)
+            break;
+    }
+}
+
+} // namespace
+
+// Whether the matrix-core kernel takes this shape: weights resident in LDS, enough work to
+// be compute-bound (small M or K leave the VALU kernel at the memory bound anyway).
+bool bg_bgemm_mfma_applies(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int32_t M)
+{
+    if (ctx->bgemm_path == 1)
+        return false;
+    const int64_t Kp = (int64_t)kwords * 64, Mp = ((int64_t)M + 15) / 16 * 16;
+    // rows are held in 8 registers, column constants of 256 columns
+    if (Kp > 512 || Mp > kMfColGroups * kMfGroup * 16 || (size_t)(Mp * (Kp + 16)) > kMfLdsLimit)
+        return false;
+    if (ctx->bgemm_path == 2)
+        return true;
+    // measured on MI355X: the fixed cost (widening the weights, one LDS copy of them per
+    // workgroup) is repaid from about 2 x 10^5 rows on; 1.3x - 1.9x faster beyond
+    return n >= 200000;
+}
+
+int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
+                         int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits,
+                         int32_t M, int64_t w_stride, int epilogue, const int32_t *T,
+                         const float *alpha, void *out, int64_t out_stride)
+{
+    const int32_t ldw = kwords * 64 + 16, Mp = (M + 15) / 16 * 16;
+    const size_t w8_bytes = (size_t)Mp * ldw;
+    int rc = bg_ws_reserve(ctx, w8_bytes + (size_t)Mp * 4);
+    if (rc != BITGNN_OK)
+        return rc;
+    uint8_t *w8 = (uint8_t *)ctx->ws;
+    int32_t *pw = (int32_t *)(w8 + w8_bytes);
+    bgemm_widen_w_kernel<<<Mp, 256, 0, s>>>((const uint32_t *)wbits, w_stride * 2, kwords * 64, M,
+                                            ldw, w8, pw);
+    BG_LAUNCH_CHECK(ctx, "bgemm_widen_w");
+    const int64_t panels = (n + kMfPanel - 1) / kMfPanel;
+    const int64_t cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
+    const unsigned grid = (unsigned)(panels < cus ? panels : cus);
+#define BG_MFMA_KS(E, KS)                                                                         \
+    do {                                                                                          \
+        BG_HIP(ctx, hipFuncSetAttribute((const void *)bgemm_mfma_kernel<E, KS>,                   \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,               \
+                                        (int)w8_bytes));                                          \
+        bgemm_mfma_kernel<E, KS><<<grid, kMfWaves * 64, w8_bytes, s>>>(                           \
+            xbits, n, x_stride, K, kwords, (const uint4 *)w8, ldw, pw, M, Mp, T, alpha, out,      \
+            out_stride);                                                                          \
+    } while (0)
+#define BG_MFMA(E)                                                                                \
+    do {                                                                                          \
+        if (kwords <= 2)                                                                          \
+            BG_MFMA_KS(E, 2);                                                                     \
+        else if (kwords <= 4)                                                                     \
+            BG_MFMA_KS(E, 4);                                                                     \
+        else                                                                                      \
+            BG_MFMA_KS(E, 8);                                                                     \
+    } while (0)
+    switch (epilogue) {
+    case BITGNN_EPI_THRESH_BITS: BG_MFMA(BITGNN_EPI_THRESH_BITS); break;
+    case BITGNN_EPI_RAW_I32: BG_MFMA(BITGNN_EPI_RAW_I32); break;
+    default: BG_MFMA(BITGNN_EPI_SCALE_F32); break;
+    }
+#undef BG_MFMA_KS
+#undef BG_MFMA
+    BG_LAUNCH_CHECK(ctx, "bgemm_mfma");
+    return BITGNN_OK;
+}

@@ -14,6 +14,8 @@
 struct bitgnn_ctx {
     int device;           // -1: validation-only context
     int n_cus;            // compute units of the device
+    int bgemm_path;       // 0: choose per shape, 1: VALU kernel, 2: matrix-core kernel
+                          // (environment BITGNN_BGEMM=valu|mfma at context creation)
     uint32_t *queue;      // device word: work counter of the blocked bit-SpMM
     char err[256];
     uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
@@ -154,6 +156,11 @@ int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, co
                        int32_t M, int64_t z_stride, const float *alpha, void *out,
                        int64_t out_stride);
 
+bool bg_bgemm_mfma_applies(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int32_t M);
+int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
+                         int64_t x_stride, int32_t K, int32_t kwords, const uint64_t *wbits,
+                         int32_t M, int64_t w_stride, int epilogue, const int32_t *T,
+                         const float *alpha, void *out, int64_t out_stride);
 int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj);
 void bg_free_blocked(bitgnn_blocked *b);
 int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,

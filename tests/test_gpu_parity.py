@@ -31,6 +31,25 @@ TUNINGS = {"default": (8192, 255, 8), "csr-only": (8192, 255, 1 << 30),
            "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0)}
 
 
+@pytest.fixture(scope="module", params=["auto", "valu", "mfma"])
+def gemm_ctx(request, B):
+    """Contexts that choose the BMM kernel per shape, or always take the VALU / the
+    matrix-core kernel (the latter falls back when the weights do not fit in LDS)."""
+    import os
+    old = os.environ.get("BITGNN_BGEMM")
+    if request.param == "auto":
+        os.environ.pop("BITGNN_BGEMM", None)
+    else:
+        os.environ["BITGNN_BGEMM"] = request.param
+    c = B.Context(0)
+    if old is None:
+        os.environ.pop("BITGNN_BGEMM", None)
+    else:
+        os.environ["BITGNN_BGEMM"] = old
+    yield c
+    c.close()
+
+
 @pytest.fixture(params=list(TUNINGS))
 def tuned(request, B, ctx):
     """Every aggregation test runs on the CSR path and on the column-blocked path
@@ -169,8 +188,10 @@ def _pack_host(v):
 
 @pytest.mark.parametrize("n,K,M", [
     (1, 1, 1), (5, 63, 7), (129, 64, 64), (300, 65, 65), (1000, 100, 41), (777, 602, 128),
-    (500, 1433, 64), (2048, 512, 256), (100, 1000, 47), (4099, 128, 40), (33, 2100, 130)])
-def test_bgemm_three_epilogues(B, ctx, n, K, M):
+    (500, 1433, 64), (2048, 512, 256), (100, 1000, 47), (4099, 128, 40), (33, 2100, 130),
+    (5000, 200, 256), (6000, 512, 47), (4500, 64, 33), (300, 96, 528)])
+def test_bgemm_three_epilogues(B, gemm_ctx, n, K, M):
+    ctx = gemm_ctx
     r = np.random.default_rng(K * 1000 + M)
     x = W.pm1(r, (n, K))
     w = W.pm1(r, (K, M))
@@ -236,7 +257,8 @@ def test_bgemm_f32_binarizes_inside(B, ctx, n, K, M):
         assert rel_close(of.cpu().numpy(), orc.scale(z, alpha))
 
 
-def test_bgemm_segmented_k_with_interior_pad_bits(B, ctx):
+def test_bgemm_segmented_k_with_interior_pad_bits(B, gemm_ctx):
+    ctx = gemm_ctx
     # [self | nbr] rows: two 100-bit segments, each padded to 128 bits, K = 200
     r = np.random.default_rng(99)
     n, k_in, M = 300, 100, 70
