@@ -219,19 +219,33 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
     }
 }
 
+// `col` and `h32` are either the caller's (node ids, node-ordered rows) or the slot ids
+// and the degree-ordered compact copy of the rows.
 template <int P>
 void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj *adj,
-                    const uint32_t *h32, int64_t h_stride32, int32_t C, int32_t W32,
-                    const uint32_t *seeds, void *out, int64_t out_stride)
+                    const int32_t *col, const uint32_t *h32, int64_t h_stride32, int32_t C,
+                    int32_t W32, const uint32_t *seeds, void *out, int64_t out_stride)
 {
     if (epilogue == BITGNN_EPI_THRESH_BITS)
         bspmm_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid, kBlock, 0, s>>>(
-            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds,
-            out, out_stride);
+            adj->rowptr, col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds, out,
+            out_stride);
     else
         bspmm_kernel<P, BITGNN_EPI_RAW_I32><<<grid, kBlock, 0, s>>>(
-            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds,
-            out, out_stride);
+            adj->rowptr, col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds, out,
+            out_stride);
+}
+
+// rows in degree order, W32 words each, no padding
+__global__ void csr_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_stride32,
+                                   const int32_t *__restrict__ order, uint32_t n, int32_t W32,
+                                   uint32_t *__restrict__ hperm)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t slot = t / (uint32_t)W32;
+    const int w = (int)(t - slot * (uint32_t)W32);
+    if (slot < n)
+        hperm[t] = h32[(int64_t)order[slot] * h_stride32 + w];
 }
 
 
@@ -1115,22 +1129,36 @@ int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const
     const int64_t grid = (threads + kBlock - 1) / kBlock;
     BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm: N*C too large");
     const uint32_t *h32 = (const uint32_t *)hbits;
+    const int32_t *col = adj->col;
+    int64_t hs32 = h_stride * 2;
+    if (adj->col_slot) { // gather from a degree-ordered copy of the rows
+        const int rc = bg_ws_reserve(ctx, (size_t)threads * 4);
+        if (rc != BITGNN_OK)
+            return rc;
+        csr_permute_kernel<<<(unsigned)grid, kBlock, 0, s>>>(h32, hs32, adj->order,
+                                                             (uint32_t)adj->n, W32,
+                                                             (uint32_t *)ctx->ws);
+        BG_LAUNCH_CHECK(ctx, "csr_permute");
+        h32 = (const uint32_t *)ctx->ws;
+        hs32 = W32;
+        col = adj->col_slot;
+    }
     bg_time_begin(ctx, s);
     switch (P) {
     case 12:
-        launch_bspmm_p<12>(s, (unsigned)grid, epilogue, adj, h32, h_stride * 2, C, W32, seeds, out,
+        launch_bspmm_p<12>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
                            out_stride);
         break;
     case 16:
-        launch_bspmm_p<16>(s, (unsigned)grid, epilogue, adj, h32, h_stride * 2, C, W32, seeds, out,
+        launch_bspmm_p<16>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
                            out_stride);
         break;
     case 20:
-        launch_bspmm_p<20>(s, (unsigned)grid, epilogue, adj, h32, h_stride * 2, C, W32, seeds, out,
+        launch_bspmm_p<20>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
                            out_stride);
         break;
     default:
-        launch_bspmm_p<26>(s, (unsigned)grid, epilogue, adj, h32, h_stride * 2, C, W32, seeds, out,
+        launch_bspmm_p<26>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
                            out_stride);
         break;
     }

@@ -94,6 +94,8 @@ struct bitgnn_adj {
     int32_t *col;     // [nnz]
     int32_t *deg;     // [n]
     int32_t *order;   // [n] rows by decreasing degree
+    int32_t *col_slot; // [nnz] column indices as degree-order slots (large CSR-only graphs:
+                       // gathers from a degree-ordered copy keep the hubs' rows together)
     size_t device_bytes;
     bitgnn_blocked *blk; // null when the graph is too sparse for the blocked path
 };
