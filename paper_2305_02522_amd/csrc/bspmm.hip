@@ -255,11 +255,12 @@ __global__ void csr_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_s
 // A workgroup of 16 wavefronts walks the column blocks its slices touch.  For a
 // block it copies the (degree-ordered) activation rows of the block's nodes into
 // LDS with coalesced 16-byte accesses; then every lane streams the 16-bit local
-// ids of ITS row part, lane-interleaved in memory (one 8-byte load = 4 ids),
+// ids of ITS row part, lane-interleaved in memory (one 16-byte load = 8 ids),
 // gathers the 16-byte rows from LDS and adds them into bit-sliced counters of
-// 10 planes x 128 channels.  Parts never exceed 1023 entries, so 10 planes do.
+// 8 or 10 planes x 128 channels (parts never exceed 255 resp. 1023 entries).
 // Each lane writes its partial planes; the merge kernel adds the parts of a
 // node, applies the seed and the threshold (or unpacks the integers).
+
 // Counter planes of a row part: 8 when parts have at most 255 entries (the partial
 // planes of a part are then exactly one 128-byte line), else 10 (up to 1023 entries).
 static int part_planes_for(const bitgnn_blocked *b) { return b->part_len <= 255 ? 8 : 10; }
