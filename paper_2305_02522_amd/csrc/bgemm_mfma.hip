@@ -10,16 +10,17 @@
 //  - the weights, widened once per call to bytes (row stride K' + 16 so that the 16-byte
 //    operand reads of 16 columns fall into different LDS bank groups), stay in LDS for the
 //    whole life of a persistent workgroup (hence the limit M' (K' + 16) <= 144 KB);
-//  - a wavefront owns 32 rows (two A operands, widened from their packed words with
+//  - a wavefront owns 32 node rows (two operands, widened from their packed words with
 //    three VALU ops per four bytes) and walks column groups of 128: 16 accumulators of
-//    16x16, every B operand read from LDS feeds two MFMAs;
-//  - the epilogue works on the accumulator layout (lane = column, 4 rows): integers and
-//    logits are stored as 64-byte row segments, thresholded bits are gathered from wave
-//    votes into whole 64-bit words.
+//    16x16, every weight operand read from LDS feeds two MFMAs;
+//  - the weights are the MFMA's first operand, so a lane ends up with 4 consecutive columns
+//    of one node row: integers and logits leave as runs of 4, thresholded bits are built
+//    in-lane and OR-ed over the 4 lanes that share the row;
+//  - the rows of the next panel are requested while the current one is computed.
 // Against the VALU kernel (2 lane-ops per 32 bit-MACs: 629 T bit-MAC/s at peak, ~310
-// reached) the int8 MFMA peak is 2,500 T MAC/s; this kernel reaches ~590 on 2.4 M x 512 x 256
-// (widening and the bit-packing epilogue share the issue slots with the MFMAs).  It is
-// chosen when the weights fit in LDS and there are enough rows to repay the set-up.
+// reached) the int8 MFMA peak is 2,500 T MAC/s; this kernel reaches ~740 on 2.4 M x 512 x 256
+// (widening and the epilogue share the issue slots with the MFMAs).  It is chosen when the
+// weights fit in LDS and there are enough rows to repay the set-up.
 #include "common.h"
 
 namespace {
@@ -30,7 +31,10 @@ constexpr int kMfWaves = 8;            // wavefronts per workgroup
 constexpr int kMfRows = 32;            // rows per wavefront (two 16-row operands)
 constexpr int kMfPanel = kMfWaves * kMfRows;
 constexpr int kMfGroup = 8;            // column tiles of 16 per pass (128 columns)
-constexpr int kMfColGroups = 2;        // column groups whose per-lane constants stay in registers
+#ifndef BITGNN_MF_PAD
+#define BITGNN_MF_PAD 16
+#endif
+constexpr int kMfPad = BITGNN_MF_PAD;  // bytes added to a weight row in LDS (bank spreading)
 constexpr size_t kMfLdsLimit = 144 * 1024;
 
 // w8[c * ldw + k] = stored bit k of weight row c (0 beyond the kbits stored bits or M);
@@ -86,26 +90,22 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
     const int r = lane & 15, g = lane >> 4;
     for (int i = tid; i < Mp * (ldw / 16); i += kMfWaves * 64)
         wl[i] = w8g[i];
-    __syncthreads(); // the only barrier: the weights are read-only from here on
-    const char *wbytes = (const char *)wl;
+    char *wbytes = (char *)wl;
     const int64_t last = n - 1;
-    // per-lane column constants of up to kMfColGroups x kMfGroup tiles, fixed for the run:
-    // THRESH: T - K + 2 pw (a column beyond M never passes); else K - 2 pw and the scale
-    int32_t colk[kMfColGroups][kMfGroup];
-    float colf[kMfColGroups][kMfGroup];
-#pragma unroll
-    for (int cgi = 0; cgi < kMfColGroups; ++cgi)
-#pragma unroll
-        for (int t = 0; t < kMfGroup; ++t) {
-            const int c = (cgi * kMfGroup + t) * 16 + r;
-            const bool c_ok = c < M;
-            const int pwc = c_ok ? pw[c] : 0;
-            if (EPI == BITGNN_EPI_THRESH_BITS)
-                colk[cgi][t] = c_ok ? T[c] - K + 2 * pwc : 0x7FFFFFFF;
-            else
-                colk[cgi][t] = K - 2 * pwc;
-            colf[cgi][t] = (EPI == BITGNN_EPI_SCALE_F32 && c_ok) ? alpha[c] : 0.0f;
-        }
+    // column constants behind the weights in LDS, fixed for the run:
+    // THRESH: T - K + 2 pw (a column beyond M never passes); else K - 2 pw, and the scale
+    int32_t *colk = (int32_t *)(wbytes + (size_t)Mp * ldw);
+    float *colf = (float *)(colk + Mp);
+    for (int c = tid; c < Mp; c += kMfWaves * 64) {
+        const bool c_ok = c < M;
+        const int pwc = c_ok ? pw[c] : 0;
+        if (EPI == BITGNN_EPI_THRESH_BITS)
+            colk[c] = c_ok ? T[c] - K + 2 * pwc : 0x7FFFFFFF;
+        else
+            colk[c] = K - 2 * pwc;
+        colf[c] = (EPI == BITGNN_EPI_SCALE_F32 && c_ok) ? alpha[c] : 0.0f;
+    }
+    __syncthreads(); // the last barrier: weights and constants are read-only from here on
 
     // the packed words of the wavefront's two 16-row operands (clamped row and word index:
     // no load is conditional, so all of them travel together)
@@ -122,22 +122,23 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
         }
     };
 
+    // The weights go in as the MFMA's A operand (its rows = weight columns) and the node
+    // rows as B, so a lane ends up with 4 consecutive columns (4 g + j of every tile) of ONE
+    // node row (r): its own popcount applies, integers and logits leave as 16-byte stores,
+    // and the thresholded bits of a row are assembled in-lane and OR-ed over the 4 lanes
+    // that share the row.
     auto compute = [&](int64_t panel, const uint64_t (&wa)[KS], const uint64_t (&wb)[KS]) {
         const int64_t row0 = panel * kMfPanel + wave * kMfRows;
         if (row0 >= n)
             return;
-        int pxa = 0, pxb = 0;
+        int px2[2] = {0, 0}; // twice the popcount of the lane's row in either operand
 #pragma unroll
         for (int u = 0; u < KS; ++u)
             if (u < ksteps) {
-                pxa += __popcll(wa[u]);
-                pxb += __popcll(wb[u]);
+                px2[0] += 2 * __popcll(wa[u]);
+                px2[1] += 2 * __popcll(wb[u]);
             }
-#pragma unroll
-        for (int cg = 0; cg < kMfColGroups; ++cg) { // static index into the column constants
-            const int c0 = cg * kMfGroup * 16;
-            if (c0 >= Mp) // wave-uniform
-                continue;
+        for (int c0 = 0; c0 < Mp; c0 += kMfGroup * 16) {
             const int ntile = (Mp - c0) / 16 < kMfGroup ? (Mp - c0) / 16 : kMfGroup;
             v4i acc[2][kMfGroup];
 #pragma unroll
@@ -155,70 +156,62 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
                         if (t < ntile) { // wave-uniform
                             const v4i b = *(const v4i *)(wk + (size_t)t * 16 * ldw);
                             acc[0][t] =
-                                __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b, acc[0][t], 0, 0, 0);
+                                __builtin_amdgcn_mfma_i32_16x16x64_i8(b, a0, acc[0][t], 0, 0, 0);
                             acc[1][t] =
-                                __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b, acc[1][t], 0, 0, 0);
+                                __builtin_amdgcn_mfma_i32_16x16x64_i8(b, a1, acc[1][t], 0, 0, 0);
                         }
                     }
                 }
             }
-            // accumulator layout: lane = column (r), rows 4 g + j of the 16-row operand.
-            // Z = K - 2 px - 2 pw + 4 D: the column part (colk) is fixed per lane and tile.
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int px_mine = h == 0 ? pxa : pxb; // held by the lane whose r is the row
-                int px2[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    px2[j] = 2 * __shfl(px_mine, 4 * g + j, 64);
-                const int64_t rbase = row0 + 16 * h + 4 * g;
+                const int64_t row = row0 + 16 * h + r;
                 if (EPI == BITGNN_EPI_THRESH_BITS) {
-                    // bit = (4 D - 2 px >= T - K + 2 pw); lane w < 16 assembles the words of
-                    // row w = 4 g' + j': vote[t][j] bits 16 g' .. 16 g' + 15 are that row's
-                    // columns 16 t .. 16 t + 15
-                    const int gw = (lane >> 2) & 3, jw = lane & 3;
-                    const uint32_t sh = 16u * (gw & 1);
-                    uint32_t lo[kMfGroup / 4] = {}, hi[kMfGroup / 4] = {};
+                    // bit = (4 D - 2 px >= T - K + 2 pw), at position 16 t' + 4 g + j of the
+                    // 64-column word t / 4
+                    uint32_t wlo[kMfGroup / 4] = {}, whi[kMfGroup / 4] = {};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        uint32_t f[kMfGroup];
+                    for (int t = 0; t < kMfGroup; ++t) {
+                        if (t >= ntile) // wave-uniform; tiles beyond M' contribute no bits
+                            continue;
+                        const v4i ck = *(const v4i *)(colk + c0 + 16 * t + 4 * g);
+                        uint32_t nib = 0;
 #pragma unroll
-                        for (int t = 0; t < kMfGroup; ++t) {
-                            const uint64_t v = __ballot(4 * acc[h][t][j] - px2[j] >= colk[cg][t]);
-                            const uint32_t half = gw < 2 ? (uint32_t)v : (uint32_t)(v >> 32);
-                            f[t] = (half >> sh) & 0xFFFFu;
-                        }
-#pragma unroll
-                        for (int wi = 0; wi < kMfGroup / 4; ++wi) {
-                            const uint32_t l = f[4 * wi] | (f[4 * wi + 1] << 16);
-                            const uint32_t u = f[4 * wi + 2] | (f[4 * wi + 3] << 16);
-                            lo[wi] = jw == j ? l : lo[wi];
-                            hi[wi] = jw == j ? u : hi[wi];
-                        }
+                        for (int j = 0; j < 4; ++j)
+                            nib |= (4 * acc[h][t][j] - px2[h] >= ck[j]) ? (1u << j) : 0u;
+                        if ((t & 2) == 0)
+                            wlo[t / 4] |= nib << (16 * (t & 1));
+                        else
+                            whi[t / 4] |= nib << (16 * (t & 1));
                     }
-                    const int64_t row = row0 + 16 * h + lane;
 #pragma unroll
                     for (int wi = 0; wi < kMfGroup / 4; ++wi) {
+                        uint32_t lo = wlo[wi] << (4 * g), hi = whi[wi] << (4 * g);
+                        lo |= __shfl_xor(lo, 16, 64);
+                        hi |= __shfl_xor(hi, 16, 64);
+                        lo |= __shfl_xor(lo, 32, 64);
+                        hi |= __shfl_xor(hi, 32, 64);
                         const int wcolumn = c0 / 64 + wi;
-                        if (lane < 16 && row < n && wcolumn * 64 < M)
+                        if (g == 0 && row < n && wcolumn * 64 < M)
                             ((uint64_t *)out)[row * out_stride + wcolumn] =
-                                ((uint64_t)hi[wi] << 32) | lo[wi];
+                                ((uint64_t)hi << 32) | lo;
                     }
                 } else {
 #pragma unroll
                     for (int t = 0; t < kMfGroup; ++t) {
-                        const int c = c0 + 16 * t + r;
-                        const bool c_ok = t < ntile && c < M;
+                        const int c = c0 + 16 * t + 4 * g;
+                        if (t < ntile && row < n) {
+                            const v4i ck = *(const v4i *)(colk + c); // K - 2 pw here
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            // colk holds K - 2 pw here
-                            const int32_t z = 4 * acc[h][t][j] - px2[j] + colk[cg][t];
-                            if (c_ok && rbase + j < n) {
-                                if (EPI == BITGNN_EPI_RAW_I32)
-                                    ((int32_t *)out)[(rbase + j) * out_stride + c] = z;
-                                else
-                                    ((float *)out)[(rbase + j) * out_stride + c] =
-                                        colf[cg][t] * (float)z;
+                            for (int j = 0; j < 4; ++j) {
+                                const int32_t z = 4 * acc[h][t][j] - px2[h] + ck[j];
+                                if (c + j < M) {
+                                    if (EPI == BITGNN_EPI_RAW_I32)
+                                        ((int32_t *)out)[row * out_stride + c + j] = z;
+                                    else
+                                        ((float *)out)[row * out_stride + c + j] =
+                                            colf[c + j] * (float)z;
+                                }
                             }
                         }
                     }
@@ -256,14 +249,14 @@ bool bg_bgemm_mfma_applies(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int
     if (ctx->bgemm_path == 1)
         return false;
     const int64_t Kp = (int64_t)kwords * 64, Mp = ((int64_t)M + 15) / 16 * 16;
-    // rows are held in 8 registers, column constants of 256 columns
-    if (Kp > 512 || Mp > kMfColGroups * kMfGroup * 16 || (size_t)(Mp * (Kp + 16)) > kMfLdsLimit)
+    // rows are held in 8 registers; weights and column constants in LDS
+    if (Kp > 512 || (size_t)(Mp * (Kp + kMfPad + 8)) > kMfLdsLimit)
         return false;
     if (ctx->bgemm_path == 2)
         return true;
     // measured on MI355X: the fixed cost (widening the weights, one LDS copy of them per
-    // workgroup) is repaid from about 2 x 10^5 rows on; 1.3x - 1.9x faster beyond
-    return n >= 200000;
+    // workgroup) is repaid from about 10^5 rows on; 1.4x - 2.4x faster beyond
+    return n >= 100000;
 }
 
 int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
@@ -271,8 +264,9 @@ int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, 
                          int32_t M, int64_t w_stride, int epilogue, const int32_t *T,
                          const float *alpha, void *out, int64_t out_stride)
 {
-    const int32_t ldw = kwords * 64 + 16, Mp = (M + 15) / 16 * 16;
+    const int32_t ldw = kwords * 64 + kMfPad, Mp = (M + 15) / 16 * 16;
     const size_t w8_bytes = (size_t)Mp * ldw;
+    const size_t lds_bytes = w8_bytes + (size_t)Mp * 8; // + column constants
     int rc = bg_ws_reserve(ctx, w8_bytes + (size_t)Mp * 4);
     if (rc != BITGNN_OK)
         return rc;
@@ -288,8 +282,8 @@ int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, 
     do {                                                                                          \
         BG_HIP(ctx, hipFuncSetAttribute((const void *)bgemm_mfma_kernel<E, KS>,                   \
                                         hipFuncAttributeMaxDynamicSharedMemorySize,               \
-                                        (int)w8_bytes));                                          \
-        bgemm_mfma_kernel<E, KS><<<grid, kMfWaves * 64, w8_bytes, s>>>(                           \
+                                        (int)lds_bytes));                                         \
+        bgemm_mfma_kernel<E, KS><<<grid, kMfWaves * 64, lds_bytes, s>>>(                          \
             xbits, n, x_stride, K, kwords, (const uint4 *)w8, ldw, pw, M, Mp, T, alpha, out,      \
             out_stride);                                                                          \
     } while (0)
