@@ -374,7 +374,10 @@ __device__ __forceinline__ blk_ids blk_load_ids(const uint32_t *__restrict__ idx
     blk_ids r;
 #pragma unroll
     for (int j = 0; j < kGroupSteps / 8; ++j) {
-        const uint4 v = p[j];
+        // read once: marked non-temporal so that the stream does not push the
+        // activation rows out of L2
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p + j);
         r.w[4 * j + 0] = v.x;
         r.w[4 * j + 1] = v.y;
         r.w[4 * j + 2] = v.z;
@@ -488,26 +491,20 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             }
             const uint32_t base = cb * cbn;
             const uint32_t rows = n - base < cbn ? n - base : cbn;
-            // cbn <= 8192: at most 8 rows per thread, in two batches of 4 loads in flight
+            // A wavefront copies 64 consecutive rows per instruction, straight from L2 into
+            // LDS (no register round trip); the ragged end of the last block goes row by row.
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const uint32_t i0 = tid + (half * 4 + 0) * kBlkThreads;
-                const uint32_t i1 = tid + (half * 4 + 1) * kBlkThreads;
-                const uint32_t i2 = tid + (half * 4 + 2) * kBlkThreads;
-                const uint32_t i3 = tid + (half * 4 + 3) * kBlkThreads;
-                const uint4 st0 = hperm[base + (i0 < rows ? i0 : 0u)];
-                const uint4 st1 = hperm[base + (i1 < rows ? i1 : 0u)];
-                const uint4 st2 = hperm[base + (i2 < rows ? i2 : 0u)];
-                const uint4 st3 = hperm[base + (i3 < rows ? i3 : 0u)];
-                if (i0 < rows)
-                    hblk[i0] = st0;
-                if (i1 < rows)
-                    hblk[i1] = st1;
-                if (i2 < rows)
-                    hblk[i2] = st2;
-                if (i3 < rows)
-                    hblk[i3] = st3;
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t w0 = (uint32_t)wave * 64u + (uint32_t)k * kBlkThreads; // uniform
+                if (w0 + 64u <= rows) {
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(hperm + base + w0 + lane),
+                        (__attribute__((address_space(3))) void *)(hblk + w0), 16, 0, 0);
+                } else if (w0 + lane < rows) {
+                    hblk[w0 + lane] = hperm[base + w0 + lane];
+                }
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the copies have landed
             __syncthreads();
 #ifdef BITGNN_PROFILE
             { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
