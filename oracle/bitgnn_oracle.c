@@ -153,3 +153,59 @@ void orc_concat(const int8_t *a, int64_t Ka, const int8_t *b, int64_t Kb,
             out[i * (Ka + Kb) + Ka + k] = b[i * Kb + k];
     }
 }
+
+/* Weighted / full-precision aggregation (Section 3.1.1: the BSpMM variants with a
+ * full-precision activation operand or output, and the weighted adjacency written as
+ * a 0/1 matrix times its factorisation vectors):
+ *   Y[i][c] = r[i] * sum_{j in N(i)} f[j] * x[j][c]
+ * in double precision: the plain definition.  r or f may be NULL (= 1). */
+void orc_spmm_weighted(const int64_t *rowptr, const int32_t *col, int64_t n,
+                       const double *x, int64_t C, const double *r,
+                       const double *f, double *Y)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n; ++i) {
+        for (int64_t c = 0; c < C; ++c) {
+            double s = 0.0;
+            for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+                const int64_t j = col[k];
+                s += (f ? f[j] : 1.0) * x[j * C + c];
+            }
+            Y[i * C + c] = (r ? r[i] : 1.0) * s;
+        }
+    }
+}
+
+/* The same sum as single precision takes it when every step is rounded once: neighbour
+ * by neighbour in stored order, one multiply and one add each (no fused multiply-add),
+ * then one multiply by r[i].  This is the value that decides a bit when the output of
+ * a weighted aggregation is binarized again; `volatile` keeps the compiler from
+ * contracting or widening the steps. */
+void orc_spmm_weighted_f32(const int64_t *rowptr, const int32_t *col, int64_t n,
+                           const float *x, int64_t C, const float *r,
+                           const float *f, float *Y)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n; ++i) {
+        for (int64_t c = 0; c < C; ++c) {
+            volatile float s = 0.0f;
+            for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+                const int64_t j = col[k];
+                volatile float p = (f ? f[j] : 1.0f) * x[j * C + c];
+                s = s + p;
+            }
+            volatile float y = (r ? r[i] : 1.0f) * s;
+            Y[i * C + c] = y;
+        }
+    }
+}
+
+/* Re-binarization of a full-precision value: +1 if y >= tau_c else -1
+ * (Section 2.2 with a threshold in place of 0; ties give +1). */
+void orc_rebin_f32(const float *y, int64_t n, int64_t C, const float *tau,
+                   int8_t *v)
+{
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t c = 0; c < C; ++c)
+            v[i * C + c] = (y[i * C + c] >= tau[c]) ? 1 : -1;
+}

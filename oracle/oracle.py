@@ -32,7 +32,7 @@ def build(force: bool = False) -> str:
     run on whatever host the GPU machine has)."""
     if force or not os.path.exists(_LIB) or \
             os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared",
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
                                "-std=c99", "-Wall", "-o", _LIB, _SRC])
     return _LIB
 
@@ -163,6 +163,51 @@ def spmm_i64(rowptr: np.ndarray, col: np.ndarray, z: np.ndarray,
     rp = rowptr[lo:hi + 1]
     lib().orc_spmm_i64(_p(rp), _p(col), I64(hi - lo), _p(z), I64(m), _p(y))
     return y
+
+
+def spmm_weighted(rowptr: np.ndarray, col: np.ndarray, x: np.ndarray,
+                  r: Optional[np.ndarray] = None, f: Optional[np.ndarray] = None) -> np.ndarray:
+    """Y[i] = r_i * sum_{j in N(i)} f_j x[j] in float64: the plain definition of the
+    weighted / full-precision aggregation (Section 3.1.1).  x: any real [n, C]."""
+    x = _c(x, np.float64)
+    rowptr = _c(rowptr, np.int64)
+    col = _c(col, np.int32)
+    n, c = len(rowptr) - 1, x.shape[1]
+    r = None if r is None else _c(r, np.float64)
+    f = None if f is None else _c(f, np.float64)
+    y = np.empty((n, c), dtype=np.float64)
+    lib().orc_spmm_weighted(_p(rowptr), _p(col), I64(n), _p(x), I64(c), _p(r), _p(f), _p(y))
+    return y
+
+
+def spmm_weighted_f32(rowptr: np.ndarray, col: np.ndarray, x: np.ndarray,
+                      r: Optional[np.ndarray] = None, f: Optional[np.ndarray] = None,
+                      rows: Optional[Tuple[int, int]] = None) -> np.ndarray:
+    """The same sum in float32, every step rounded once, neighbours in stored order:
+    the value that decides a bit when the result is binarized again."""
+    x = _c(x, np.float32)
+    rowptr = _c(rowptr, np.int64)
+    col = _c(col, np.int32)
+    lo, hi = (0, len(rowptr) - 1) if rows is None else rows
+    c = x.shape[1]
+    r = None if r is None else _c(np.asarray(r, dtype=np.float32)[lo:hi], np.float32)
+    f = None if f is None else _c(f, np.float32)
+    y = np.empty((hi - lo, c), dtype=np.float32)
+    rp = rowptr[lo:hi + 1]
+    lib().orc_spmm_weighted_f32(_p(rp), _p(col), I64(hi - lo), _p(x), I64(c), _p(r), _p(f),
+                                _p(y))
+    return y
+
+
+def rebin_f32(y: np.ndarray, tau: np.ndarray) -> np.ndarray:
+    """+1 where y >= tau_c else -1, on float32 values."""
+    y = _c(y, np.float32)
+    tau = _c(tau, np.float32)
+    n, c = y.shape
+    assert tau.shape == (c,)
+    v = np.empty((n, c), dtype=np.int8)
+    lib().orc_rebin_f32(_p(y), I64(n), I64(c), _p(tau), _p(v))
+    return v
 
 
 def scale(y: np.ndarray, alpha: np.ndarray) -> np.ndarray:

@@ -360,3 +360,88 @@ def test_alg1_emulator_equals_oracle(n, e, c, seed):
         for ch in range(c):
             bit = (out[i][ch // 32] >> (ch % 32)) & 1
             assert bit == (1 if expect[i, ch] > 0 else 0)
+
+
+# ------------------------------------------- weighted / full-precision aggregation
+def _small_graph(seed, n=60, e=400, flags=W.ADJ_SYMMETRIZE | W.ADJ_ADD_SELF_LOOPS):
+    r = _rng(seed)
+    src, dst = W.random_graph(r, n, e)
+    rp, col = orc.adjacency(src, dst, n, flags)
+    return r, n, rp, col
+
+
+def test_weighted_spmm_equals_dense_matmul_with_factor_vectors():
+    """diag(r) A diag(f) X by numpy's dense float64 matmul (an independent routine);
+    a transposed adjacency, a swapped r / f or a dropped factor fails it."""
+    r, n, rp, col = _small_graph(1, flags=0)          # directed: A != A^T
+    a = np.zeros((n, n))
+    for i in range(n):
+        a[i, col[rp[i]:rp[i + 1]]] = 1.0
+    x = r.standard_normal((n, 9))
+    rv, fv = r.uniform(0.5, 2.0, n), r.uniform(0.5, 2.0, n)
+    want = (rv[:, None] * a * fv[None, :]) @ x
+    assert np.allclose(orc.spmm_weighted(rp, col, x, rv, fv), want, rtol=1e-13, atol=1e-13)
+    assert np.allclose(orc.spmm_weighted(rp, col, x, None, fv), (a * fv[None, :]) @ x,
+                       rtol=1e-13, atol=1e-13)
+    assert np.allclose(orc.spmm_weighted(rp, col, x, rv, None), (rv[:, None] * a) @ x,
+                       rtol=1e-13, atol=1e-13)
+    assert not np.allclose(orc.spmm_weighted(rp, col, x, fv, rv), want)
+
+
+def test_weighted_spmm_unit_factors_on_pm1_is_the_integer_aggregation():
+    """r = f = 1 on +-1 activations: both the float64 and the step-rounded float32 sum are
+    the exact integers of the 0/1 x +-1 aggregation (Section 3.2.2)."""
+    r, n, rp, col = _small_graph(2)
+    v = W.pm1(r, (n, 33))
+    s = orc.spmm_pm1(rp, col, v)
+    assert np.array_equal(orc.spmm_weighted(rp, col, v), s.astype(np.float64))
+    assert np.array_equal(orc.spmm_weighted_f32(rp, col, v), s.astype(np.float32))
+
+
+def test_weighted_spmm_closed_forms_regular_graph_and_mean():
+    """k-regular ring with self-loops, symmetric normalisation r = f = deg^-1/2: constant
+    input 1 gives exactly 1 per node; mean (r = 1/deg) of a constant is the constant; the
+    normalised operator is symmetric: <u, P v> = <P u, v>."""
+    n, k = 40, 3
+    src = np.repeat(np.arange(n), k).astype(np.int32)
+    dst = ((src + np.tile(np.arange(1, k + 1), n)) % n).astype(np.int32)
+    rp, col = orc.adjacency(src, dst, n, W.ADJ_SYMMETRIZE | W.ADJ_ADD_SELF_LOOPS)
+    deg = orc.degrees(rp).astype(np.float64)
+    assert np.all(deg == 2 * k + 1)
+    dinv = deg ** -0.5
+    ones = np.ones((n, 2))
+    assert np.allclose(orc.spmm_weighted(rp, col, ones, dinv, dinv), 1.0, rtol=0, atol=1e-15)
+    r, _, rp2, col2 = _small_graph(3)
+    deg2 = orc.degrees(rp2).astype(np.float64)
+    c = np.full((len(deg2), 3), 2.5)
+    assert np.allclose(orc.spmm_weighted(rp2, col2, c, 1.0 / deg2, None), 2.5, rtol=1e-15)
+    d2 = deg2 ** -0.5
+    u, v = r.standard_normal((len(deg2), 1)), r.standard_normal((len(deg2), 1))
+    pu, pv = orc.spmm_weighted(rp2, col2, u, d2, d2), orc.spmm_weighted(rp2, col2, v, d2, d2)
+    assert abs(float((u * pv).sum() - (pu * v).sum())) < 1e-12
+
+
+def test_weighted_spmm_f32_steps_handworked_and_error_bound():
+    """Order and rounding of the float32 variant on a hand-worked row: (2^24 + 1) - 2^24
+    summed left to right in float32 is 1 only if the big terms cancel first; and on random
+    inputs the float32 value stays within deg * eps * sum|terms| of the float64 one."""
+    rp = np.array([0, 3], dtype=np.int64)
+    x = np.array([[16777216.0], [1.0], [-16777216.0]], dtype=np.float32)
+    col = np.array([0, 1, 2], dtype=np.int32)       # 2^24 + 1 rounds to 2^24, then - 2^24 = 0
+    assert orc.spmm_weighted_f32(rp, col, x)[0, 0] == 0.0
+    col = np.array([0, 2, 1], dtype=np.int32)       # 2^24 - 2^24 + 1 = 1
+    assert orc.spmm_weighted_f32(rp, col, x)[0, 0] == 1.0
+    assert orc.spmm_weighted(rp, col, x)[0, 0] == 1.0
+    f = np.array([3.0, 0.5, 3.0], dtype=np.float32)  # factors multiply the column, r the row
+    assert orc.spmm_weighted_f32(rp, col, x, np.array([2.0], np.float32), f)[0, 0] == 1.0
+    r, n, rp, col = _small_graph(4, n=200, e=4000)
+    xx = r.standard_normal((n, 7)).astype(np.float32)
+    fv = r.uniform(0.1, 1.0, n).astype(np.float32)
+    rv = r.uniform(0.1, 1.0, n).astype(np.float32)
+    y64 = orc.spmm_weighted(rp, col, xx, rv, fv)
+    y32 = orc.spmm_weighted_f32(rp, col, xx, rv, fv)
+    mag = orc.spmm_weighted(rp, col, np.abs(xx), rv, fv)
+    deg = orc.degrees(rp)[:, None]
+    assert np.all(np.abs(y32 - y64) <= (deg + 2) * 2.0 ** -24 * mag + 1e-30)
+    tau = np.zeros(7, dtype=np.float32)
+    assert np.array_equal(orc.rebin_f32(y32, tau), np.where(y32 >= 0, 1, -1))
