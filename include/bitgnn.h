@@ -197,6 +197,24 @@ int bitgnn_spmm_i32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const 
                     int32_t M, int64_t z_stride, int64_t z_abs_bound, const float *alpha,
                     void *out, int64_t out_stride);
 
+/* Weighted / full-precision aggregation: the BSpMM variants of Section 3.1.1 whose
+ * activation operand or output is full precision, and the weighted adjacency as the
+ * 0/1 matrix times its factorisation vectors:
+ *   Y[i][c] = r[i] * sum_{j in N(i)} f[j] * x[j][c],  c < C.
+ * x: x_is_bits == 0: float [N][ldx];  x_is_bits != 0: packed +-1 rows, uint64 [N][ldx]
+ *    (pad bits zero).  r, f: float [N] or NULL (= 1): D^-1/2 A D^-1/2 is
+ *    r = f = deg^-1/2, the mean aggregator is r = 1/deg.
+ * epilogue SCALE_F32:   out = float [N][ldo] <- Y
+ *          THRESH_BITS: out = uint64 [N][ldo], ceil(C/64) words per row,
+ *                       bit c = (Y >= tau[c]); needs tau (float [C]); pad bits zero.
+ * Arithmetic: float, one rounded multiply and one rounded add per neighbour in the
+ * order of bitgnn_adj_csr's column indices, then one multiply by r[i]; no fused
+ * multiply-add.  Results are therefore bit-reproducible.  x and out must not overlap.
+ * All pointers are device pointers owned by the caller; asynchronous on `stream`. */
+int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const void *x,
+                    int x_is_bits, int32_t C, int64_t ldx, const float *r, const float *f,
+                    int epilogue, const float *tau, void *out, int64_t ldo);
+
 /* ---- layers (Section 3.1.2 high-level functions; Table 3 caption recipe) - */
 
 /* GCN hidden layer, BMM.xBB + BSpMM.BBB:

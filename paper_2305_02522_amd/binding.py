@@ -65,6 +65,8 @@ _SIGNATURES = {
                                     _vp, _vp, _i64]),
     "bitgnn_bspmm": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
     "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
+    "bitgnn_spmm_f32": (_int, [_vp, _vp, _vp, _vp, _int, _i32, _i64, _vp, _vp, _int, _vp, _vp,
+                               _i64]),
     "bitgnn_gcn_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp, _vp,
                                 _vp, _vp, _i64]),
     "bitgnn_gcn_out_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp,
@@ -238,6 +240,13 @@ def spmm_i32(ctx: Context, adj: Optional[Adjacency], Z, M, z_stride, z_abs_bound
              out_stride):
     ctx.check(_lib.bitgnn_spmm_i32(ctx.handle, _stream(), adj.handle if adj else None, _ptr(Z), M,
                                    z_stride, z_abs_bound, _ptr(alpha), _ptr(out), out_stride))
+
+
+def spmm_f32(ctx: Context, adj: Optional[Adjacency], x, x_is_bits, C, ldx, r, f, epilogue, tau,
+             out, ldo):
+    ctx.check(_lib.bitgnn_spmm_f32(ctx.handle, _stream(), adj.handle if adj else None, _ptr(x),
+                                   int(x_is_bits), C, ldx, _ptr(r), _ptr(f), epilogue, _ptr(tau),
+                                   _ptr(out), ldo))
 
 
 def gcn_layer(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride, T_mm, T_agg,

@@ -363,6 +363,68 @@ def test_spmm_i32(B, ctx, n, e, M):
     adj.close()
 
 
+# ------------------------------------------- weighted / full-precision aggregation
+@pytest.mark.parametrize("n,e,C,flags,hubs", [
+    (1, 0, 1, W.ADJ_ADD_SELF_LOOPS, 0), (9, 20, 7, SYM_LOOPS, 0), (257, 3000, 33, W.ADJ_SYMMETRIZE, 0),
+    (1000, 20000, 64, SYM_LOOPS, 0), (3000, 40000, 100, 0, 0), (5000, 100000, 128, SYM_LOOPS, 2),
+    (1500, 9000, 300, W.ADJ_SYMMETRIZE, 0), (700, 300, 65, 0, 0)])
+def test_spmm_f32_variants(B, ctx, n, e, C, flags, hubs):
+    """Float and bit activations, with and without factor vectors (symmetric normalisation,
+    mean), float and re-binarized output.  The float output must equal the step-rounded
+    float32 oracle bit for bit (same order, same roundings) and lie within the bound
+    (deg + 2) * 2^-24 * sum|terms| of the float64 definition; the bits are compared after
+    the same float32 decision."""
+    adj, rp, col, r = _graph(B, ctx, n, e, flags, n + C + 1, hubs)
+    deg = np.maximum(orc.degrees(rp), 1).astype(np.float64)
+    dinv = (deg ** -0.5).astype(np.float32)
+    mean = (1.0 / deg).astype(np.float32)
+    xf = r.standard_normal((n, C)).astype(np.float32)
+    v = W.pm1(r, (n, C))
+    cw = (C + 63) // 64
+    tau = r.uniform(-0.5, 0.5, C).astype(np.float32)
+    for x_bits, rv, fv in ((False, None, None), (False, dinv, dinv), (False, mean, None),
+                           (True, dinv, dinv), (True, None, None), (True, mean, None)):
+        x_host = v.astype(np.float32) if x_bits else xf
+        x_dev = _pack_host(v) if x_bits else dev(xf)
+        ldx = cw if x_bits else C
+        want32 = orc.spmm_weighted_f32(rp, col, x_host, rv, fv)
+        want64 = orc.spmm_weighted(rp, col, x_host, rv, fv)
+        mag = orc.spmm_weighted(rp, col, np.abs(x_host), rv, fv)
+        out = torch.full((n, C + 3), 777.0, dtype=torch.float32, device="cuda")
+        B.spmm_f32(ctx, adj, x_dev, x_bits, C, ldx, None if rv is None else dev(rv),
+                   None if fv is None else dev(fv), B.EPI_SCALE_F32, None, out, C + 3)
+        ob = torch.full((n, cw + 1), -1, dtype=torch.int64, device="cuda")
+        B.spmm_f32(ctx, adj, x_dev, x_bits, C, ldx, None if rv is None else dev(rv),
+                   None if fv is None else dev(fv), B.EPI_THRESH_BITS, dev(tau), ob, cw + 1)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :C], want32)
+        assert np.all(got[:, C:] == 777.0)
+        bound = (orc.degrees(rp)[:, None] + 2) * 2.0 ** -24 * mag + 1e-30
+        assert np.all(np.abs(got[:, :C].astype(np.float64) - want64) <= bound)
+        gb = words_np(ob)
+        assert np.array_equal(gb[:, :cw], orc.to_words(orc.rebin_f32(want32, tau)))
+        assert np.all(gb[:, cw] == np.uint64(0xFFFFFFFFFFFFFFFF))
+        if x_bits and rv is None:      # unit factors on bits: the exact integers of the bit path
+            assert np.array_equal(got[:, :C], orc.spmm_pm1(rp, col, v).astype(np.float32))
+    adj.close()
+
+
+def test_spmm_f32_rejects_bad_arguments(B, ctx):
+    adj, rp, col, r = _graph(B, ctx, 50, 200, SYM_LOOPS, 5)
+    x = torch.zeros((50, 8), dtype=torch.float32, device="cuda")
+    out = torch.zeros((50, 8), dtype=torch.float32, device="cuda")
+    for args, code in (((x, 0, 8, 7, None, None, B.EPI_SCALE_F32, None, out, 8), B.ERR_INVALID_ARG),
+                       ((x, 0, 8, 8, None, None, B.EPI_RAW_I32, None, out, 8), B.ERR_INVALID_ARG),
+                       ((x, 0, 8, 8, None, None, B.EPI_THRESH_BITS, None, out, 8), B.ERR_INVALID_ARG),
+                       ((x.data_ptr() + 2, 0, 8, 8, None, None, B.EPI_SCALE_F32, None, out, 8),
+                        B.ERR_ALIGNMENT)):
+        with pytest.raises(B.BitgnnError) as ex:
+            B.spmm_f32(ctx, adj, *args)
+        assert ex.value.code == code
+    adj.close()
+
+
 # ------------------------------------------------------------------ whole models
 def _run_model(B, ctx, wl):
     adj = B.adj_build(ctx, dev(wl.src), dev(wl.dst), len(wl.src), wl.n, wl.adj_flags)
