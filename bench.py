@@ -128,6 +128,52 @@ def cpu_baseline(wl, rows):
     return work / secs, secs, orc.max_threads()
 
 
+def bench_spmm_f32(args, np, torch, B, ctx, adj, wl):
+    """D^-1/2 A D^-1/2 X on the workload's graph, X float32 with the first hidden width
+    (full-precision aggregation) and X as packed bits (weighted binary aggregation): one
+    JSON line.  Bytes a launch must move: the column ids and the factor of every stored
+    non-zero once, every activation row once, the output once; the gathers of rows that
+    follow are served by the caches or re-read."""
+    n, nnz, C = wl.n, adj.nnz, int(wl.dims[1])
+    r = np.random.default_rng(7)
+    import ctypes
+    deg = torch.empty(n, dtype=torch.int32, device="cuda")
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    assert hip.hipMemcpy(deg.data_ptr(), adj.csr_pointers()[2], 4 * n, 3) == 0
+    dinv = (torch.clamp(deg.to(torch.float64), min=1.0) ** -0.5).to(torch.float32)
+    xf = torch.as_tensor(r.standard_normal((n, C)).astype(np.float32), device="cuda")
+    xb = torch.as_tensor(r.integers(-2**62, 2**62, size=(n, (C + 63) // 64)), device="cuda")
+    out = torch.empty((n, C), dtype=torch.float32, device="cuda")
+    res = {}
+    for name, x, bits, ldx in (("f32", xf, 0, C), ("bits", xb, 1, (C + 63) // 64)):
+        for _ in range(max(1, args.warmup)):
+            B.spmm_f32(ctx, adj, x, bits, C, ldx, dinv, dinv, B.EPI_SCALE_F32, None, out, C)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            B.spmm_f32(ctx, adj, x, bits, C, ldx, dinv, dinv, B.EPI_SCALE_F32, None, out, C)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        row_bytes = 8 * ((C + 63) // 64) if bits else 4 * C
+        alg = nnz * 8 + n * (row_bytes + 4 * C + 12)
+        res[name] = {"ms": round(ms, 4), "gather_bytes": nnz * row_bytes,
+                     "roofline": {"bound": "hbm", "achieved": round(alg / ms / 1e6, 1),
+                                  "peak": 8000.0, "unit": "GB/s",
+                                  "frac": round(alg / ms / 1e6 / 8000.0, 4), "traffic": None}}
+        log(f"spmm_f32 {name}: {ms:.3f} ms, gathers {nnz * row_bytes / ms / 1e6:.0f} GB/s")
+    print(json.dumps({
+        "metric": "weighted aggregation D^-1/2 A D^-1/2 X (G edge-channel MAC/s), float activations",
+        "value": round(nnz * C / res["f32"]["ms"] / 1e6, 1), "unit": "G edge-channel MAC/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["f32"]["ms"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.config} {wl.name}", "N": n, "nnz": nnz, "C": C},
+        "roofline": res["f32"]["roofline"], "bits_activations": res["bits"]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +184,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1 << 30,
                     help="rows of the workload the CPU oracle is timed on (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--op", choices=["model", "spmm_f32"], default="model",
+                    help="model: the binary GNN forward pass (the headline metric); spmm_f32: "
+                    "the symmetric-normalised full-precision aggregation on the same graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -164,6 +213,8 @@ def main():
     del src, dst
     log(f"adjacency: nnz={adj.nnz} max_degree={adj.max_degree} build {build_ms:.1f} ms "
         f"blocked={adj.blocked_info()}")
+    if args.op == "spmm_f32":
+        return bench_spmm_f32(args, np, torch, B, ctx, adj, wl)
     model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
     x = torch.as_tensor(wl.x, device="cuda").to(torch.float32)
     torch.cuda.synchronize()

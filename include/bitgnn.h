@@ -254,6 +254,25 @@ int bitgnn_sage_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                           int64_t w_stride, const int32_t *T_agg, const float *alpha,
                           float *logits, int64_t ldo);
 
+/* The two hidden layers with a weighted adjacency diag(r) A diag(f) (Section 3.1.1:
+ * factorisation vectors; r = f = deg^-1/2: symmetric normalisation, r = 1/deg: mean
+ * aggregator).  r, f: float [N] or NULL (= 1); tau_agg: float thresholds of the
+ * aggregation, one per aggregated channel.  The weighted sum is bitgnn_spmm_f32's.
+ *   GCN:  h = (xbits W >= T_mm) ; out = (r .* (A_hat (f .* h)) >= tau_agg)
+ *   SAGE: nb = (r .* (A (f .* self)) >= tau_agg) ; out = ([self | nb] W >= T_mm)
+ * Other arguments as in bitgnn_gcn_layer / bitgnn_sage_layer. */
+int bitgnn_gcn_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                              const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
+                              const uint64_t *wbits, int32_t M, int64_t w_stride,
+                              const int32_t *T_mm, const float *r, const float *f,
+                              const float *tau_agg, uint64_t *tmp_bits, uint64_t *out_bits,
+                              int64_t out_stride);
+int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                               uint64_t *cat_bits, int32_t K_in, const uint64_t *wbits, int32_t M,
+                               int64_t w_stride, const float *r, const float *f,
+                               const float *tau_agg, const int32_t *T_mm, uint64_t *out_bits,
+                               int64_t out_stride);
+
 #ifdef __cplusplus
 }
 #endif

@@ -260,6 +260,25 @@ def gcn_hidden_layer(rowptr, col, v, w, t_mm, t_agg) -> np.ndarray:
     return _spmm_rebin(rowptr, col, h, t_agg)
 
 
+def gcn_hidden_layer_norm(rowptr, col, v, w, t_mm, r, f, tau_agg) -> np.ndarray:
+    """h = bin_{t_mm}(v W);  out = bin_{tau}(diag(r) A_hat diag(f) h): the GCN layer with a
+    weighted (e.g. symmetrically normalised) adjacency through its factor vectors
+    (Section 3.1.1); the weighted sum is taken in float32, step by step."""
+    h = _bmm_rebin(v, w, t_mm)
+    return rebin_f32(spmm_weighted_f32(rowptr, col, h, r, f), tau_agg)
+
+
+def sage_hidden_layer_mean(rowptr, col, v, w, rmean, tau_agg, t_mm) -> np.ndarray:
+    """nb = bin_{tau}(mean_{j in N(i)} v_j) with rmean = 1/deg (the mean aggregator of
+    Section 2.1);  out = bin_{t_mm}([v | nb] W)."""
+    nb = rebin_f32(spmm_weighted_f32(rowptr, col, v, rmean, None), tau_agg)
+    out = np.empty((v.shape[0], w.shape[1]), dtype=np.int8)
+    for lo in range(0, v.shape[0], _CHUNK):
+        cat = concat(v[lo:lo + _CHUNK], nb[lo:lo + _CHUNK])
+        out[lo:lo + _CHUNK] = rebin(bmm(cat, w), t_mm)
+    return out
+
+
 def gcn_out_layer(rowptr, col, v, w, alpha) -> np.ndarray:
     """Z = v W (integers);  Y = A_hat Z;  logits = alpha * Y."""
     n = v.shape[0]

@@ -74,6 +74,10 @@ _SIGNATURES = {
     "bitgnn_sage_layer": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp, _vp, _i64]),
     "bitgnn_sage_out_layer": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp, _vp,
                                      _i64]),
+    "bitgnn_gcn_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64,
+                                         _vp, _vp, _vp, _vp, _vp, _vp, _i64]),
+    "bitgnn_sage_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp,
+                                          _vp, _vp, _vp, _i64]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -262,6 +266,21 @@ def gcn_out_layer(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_str
     ctx.check(_lib.bitgnn_gcn_out_layer(ctx.handle, _stream(), adj.handle if adj else None,
                                         _ptr(xbits), x_stride, K, kwords, _ptr(wbits), M, w_stride,
                                         _ptr(alpha), _ptr(tmp_i32), _ptr(logits), ldo))
+
+
+def gcn_layer_weighted(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride, T_mm,
+                       r, f, tau_agg, tmp_bits, out_bits, out_stride):
+    ctx.check(_lib.bitgnn_gcn_layer_weighted(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(xbits), x_stride, K, kwords,
+        _ptr(wbits), M, w_stride, _ptr(T_mm), _ptr(r), _ptr(f), _ptr(tau_agg), _ptr(tmp_bits),
+        _ptr(out_bits), out_stride))
+
+
+def sage_layer_weighted(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, r, f, tau_agg,
+                        T_mm, out_bits, out_stride):
+    ctx.check(_lib.bitgnn_sage_layer_weighted(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(cat_bits), K_in, _ptr(wbits), M,
+        w_stride, _ptr(r), _ptr(f), _ptr(tau_agg), _ptr(T_mm), _ptr(out_bits), out_stride))
 
 
 def sage_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg, T_mm, out_bits,

@@ -161,3 +161,71 @@ extern "C" int bitgnn_sage_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn
     return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
                            BITGNN_EPI_SCALE_F32, nullptr, alpha, logits, ldo);
 }
+
+// The same two layers with a weighted adjacency, diag(r) A diag(f) (Section 3.1.1: a
+// weighted adjacency is the 0/1 matrix times its factorisation vectors): r = f = deg^-1/2
+// is the symmetric normalisation of GCN, r = 1/deg the mean aggregator of GraphSAGE.  The
+// aggregation is the step-rounded float sum of bitgnn_spmm_f32 on the packed +-1 rows,
+// binarized again with float thresholds.
+extern "C" int bitgnn_gcn_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                         const uint64_t *xbits, int64_t x_stride, int32_t K,
+                                         int32_t kwords, const uint64_t *wbits, int32_t M,
+                                         int64_t w_stride, const int32_t *T_mm, const float *r,
+                                         const float *f, const float *tau_agg, uint64_t *tmp_bits,
+                                         uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_layer_weighted: adj is null");
+    const int64_t n = adj->n;
+    const int64_t mw = ((int64_t)M + 63) / 64;
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                            BITGNN_EPI_THRESH_BITS, T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_spmm_f32(ctx, adj, tmp_bits, 1, M, mw, r, f, BITGNN_EPI_THRESH_BITS, tau_agg,
+                           out_bits, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                         BITGNN_EPI_THRESH_BITS, T_mm, nullptr, tmp_bits, mw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_spmm_f32(ctx, s, adj, tmp_bits, 1, M, mw, r, f, BITGNN_EPI_THRESH_BITS,
+                              tau_agg, out_bits, out_stride);
+}
+
+extern "C" int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                          uint64_t *cat_bits, int32_t K_in, const uint64_t *wbits,
+                                          int32_t M, int64_t w_stride, const float *r,
+                                          const float *f, const float *tau_agg,
+                                          const int32_t *T_mm, uint64_t *out_bits,
+                                          int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_layer_weighted: adj is null");
+    BG_REQUIRE(ctx, K_in >= 1 && K_in <= (1 << 29), BITGNN_ERR_INVALID_ARG,
+               "bitgnn_sage_layer_weighted: K_in=%d", K_in);
+    BG_REQUIRE(ctx, cat_bits, BITGNN_ERR_INVALID_ARG, "bitgnn_sage_layer_weighted: cat_bits is null");
+    const int64_t n = adj->n;
+    const int32_t kw = (K_in + 63) / 64;
+    int rc = bg_check_spmm_f32(ctx, adj, cat_bits, 1, K_in, 2 * kw, r, f, BITGNN_EPI_THRESH_BITS,
+                               tau_agg, cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_bgemm(ctx, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                        BITGNN_EPI_THRESH_BITS, T_mm, nullptr, out_bits, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_spmm_f32(ctx, s, adj, cat_bits, 1, K_in, 2 * kw, r, f, BITGNN_EPI_THRESH_BITS,
+                            tau_agg, cat_bits + kw, 2 * kw);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
+                           BITGNN_EPI_THRESH_BITS, T_mm, nullptr, out_bits, out_stride);
+}

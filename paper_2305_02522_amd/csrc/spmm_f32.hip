@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void spmm_f32_kernel(
             const uint32_t cnt = end - k0 < 64u ? end - k0 : 64u;
             const uint32_t jl = (uint32_t)col[k0 + (lane < cnt ? lane : cnt - 1)];
             const float fl = f ? f[jl] : 1.0f;
-            // four neighbours per turn: their rows are requested together, then added in
+            // kAhead neighbours per turn: their rows are requested together, then added in
             // order (a turn past the end repeats the last neighbour and drops it)
             for (uint32_t t = 0; t < cnt; t += kAhead) {
                 float fq[kAhead], xq[kAhead][kTiles];
@@ -113,10 +113,9 @@ __global__ __launch_bounds__(256) void spmm_f32_kernel(
 
 } // namespace
 
-extern "C" int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const void *x,
-                               int x_is_bits, int32_t C, int64_t ldx, const float *r,
-                               const float *f, int epilogue, const float *tau, void *out,
-                               int64_t ldo)
+int bg_check_spmm_f32(bitgnn_ctx *ctx, const bitgnn_adj *adj, const void *x, int x_is_bits,
+                      int32_t C, int64_t ldx, const float *r, const float *f, int epilogue,
+                      const float *tau, const void *out, int64_t ldo)
 {
     if (!ctx)
         return BITGNN_ERR_INVALID_ARG;
@@ -126,7 +125,9 @@ extern "C" int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *
                epilogue);
     const int64_t cw = ((int64_t)C + 63) / 64;
     const bool bits_out = epilogue == BITGNN_EPI_THRESH_BITS;
-    BG_REQUIRE(ctx, C >= 1 && ldx >= (x_is_bits ? cw : (int64_t)C) && ldo >= (bits_out ? cw : (int64_t)C),
+    BG_REQUIRE(ctx,
+               C >= 1 && ldx >= (x_is_bits ? cw : (int64_t)C) &&
+                   ldo >= (bits_out ? cw : (int64_t)C),
                BITGNN_ERR_INVALID_ARG, "bitgnn_spmm_f32: C=%d ldx=%lld ldo=%lld", C, (long long)ldx,
                (long long)ldo);
     BG_REQUIRE(ctx, x && out && (!bits_out || tau), BITGNN_ERR_INVALID_ARG,
@@ -136,10 +137,16 @@ extern "C" int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *
                    bg_aligned(r, 4) && bg_aligned(f, 4) && bg_aligned(tau, 4),
                BITGNN_ERR_ALIGNMENT, "bitgnn_spmm_f32: misaligned pointer");
     BG_REQUIRE(ctx, adj->n < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_spmm_f32: N too large");
-    BG_NEED_DEVICE(ctx);
+    return BITGNN_OK;
+}
+
+int bg_launch_spmm_f32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const void *x,
+                       int x_is_bits, int32_t C, int64_t ldx, const float *r, const float *f,
+                       int epilogue, const float *tau, void *out, int64_t ldo)
+{
     if (adj->n == 0)
         return BITGNN_OK;
-    hipStream_t s = (hipStream_t)stream;
+    const bool bits_out = epilogue == BITGNN_EPI_THRESH_BITS;
     const unsigned grid = (unsigned)((adj->n + 3) / 4);
 #define BG_SPMM_F32(XB, BO)                                                                       \
     spmm_f32_kernel<XB, BO><<<grid, 256, 0, s>>>(adj->rowptr, adj->col, adj->order,              \
@@ -160,4 +167,17 @@ extern "C" int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *
 #undef BG_SPMM_F32
     BG_LAUNCH_CHECK(ctx, "bitgnn_spmm_f32");
     return BITGNN_OK;
+}
+
+extern "C" int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const void *x,
+                               int x_is_bits, int32_t C, int64_t ldx, const float *r,
+                               const float *f, int epilogue, const float *tau, void *out,
+                               int64_t ldo)
+{
+    int rc = bg_check_spmm_f32(ctx, adj, x, x_is_bits, C, ldx, r, f, epilogue, tau, out, ldo);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    return bg_launch_spmm_f32(ctx, (hipStream_t)stream, adj, x, x_is_bits, C, ldx, r, f, epilogue,
+                              tau, out, ldo);
 }

@@ -527,6 +527,45 @@ def test_gcn_out_layer_digit_counts(B, ctx, n, e, K, M, kind):
     adj.close()
 
 
+@pytest.mark.parametrize("n,e,K,M", [(300, 2500, 70, 40), (4000, 60000, 128, 128),
+                                     (2500, 30000, 200, 65)])
+def test_weighted_layers(B, ctx, n, e, K, M):
+    """GCN layer with the symmetrically normalised adjacency and GraphSAGE layer with the
+    mean aggregator, against the oracle's compositions (same float32 steps)."""
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + K + M)
+    deg = np.maximum(orc.degrees(rp), 1).astype(np.float64)
+    dinv, mean = (deg ** -0.5).astype(np.float32), (1.0 / deg).astype(np.float32)
+    v = W.pm1(r, (n, K))
+    kw, mw = (K + 63) // 64, (M + 63) // 64
+    # GCN: K -> M
+    w = W.pm1(r, (K, M))
+    t_mm = r.integers(-4, 5, M).astype(np.int32)
+    tau = r.uniform(-0.3, 0.3, M).astype(np.float32)
+    tmp = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    out = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    B.gcn_layer_weighted(ctx, adj, _pack_host(v), kw, K, kw, _pack_host(np.ascontiguousarray(w.T)),
+                         M, kw, dev(t_mm), dev(dinv), dev(dinv), dev(tau), tmp, out, mw)
+    torch.cuda.synchronize()
+    want = orc.gcn_hidden_layer_norm(rp, col, v, w, t_mm, dinv, dinv, tau)
+    assert np.array_equal(words_np(out), orc.to_words(want))
+    # SAGE mean: [self | nb] (2K) -> M
+    w2 = W.pm1(r, (2 * K, M))
+    tau_k = r.uniform(-0.3, 0.3, K).astype(np.float32)
+    cat = np.zeros((n, 2 * kw), dtype=np.uint64)
+    cat[:, :kw] = orc.to_words(v)
+    cat_d = dev(cat.view(np.int64))
+    wt = np.ascontiguousarray(w2.T)
+    wb = dev(np.concatenate([orc.to_words(wt[:, :K]), orc.to_words(wt[:, K:])], axis=1)
+             .view(np.int64))
+    out2 = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    B.sage_layer_weighted(ctx, adj, cat_d, K, wb, M, 2 * kw, dev(mean), None, dev(tau_k),
+                          dev(t_mm), out2, mw)
+    torch.cuda.synchronize()
+    want2 = orc.sage_hidden_layer_mean(rp, col, v, w2, mean, tau_k, t_mm)
+    assert np.array_equal(words_np(out2), orc.to_words(want2))
+    adj.close()
+
+
 def test_forward_ops_equals_forward(B, ctx):
     for cfg, kw in ((4, {"n": 6000, "mean_deg": 120.0}), (3, {"n": 20000})):
         wl = W.make_workload(cfg, **kw)

@@ -445,3 +445,29 @@ def test_weighted_spmm_f32_steps_handworked_and_error_bound():
     assert np.all(np.abs(y32 - y64) <= (deg + 2) * 2.0 ** -24 * mag + 1e-30)
     tau = np.zeros(7, dtype=np.float32)
     assert np.array_equal(orc.rebin_f32(y32, tau), np.where(y32 >= 0, 1, -1))
+
+
+def test_weighted_layers_reduce_to_the_integer_layers():
+    """Unit factors and integer thresholds: the weighted GCN layer is the integer GCN layer.
+    On a k-regular graph the mean aggregator with threshold tau is the sum aggregator with
+    the integer threshold ceil(tau * k) (tau * k exact in float32)."""
+    r, n, rp, col = _small_graph(11, n=80, e=600)
+    v, w = W.pm1(r, (n, 20)), W.pm1(r, (20, 12))
+    t_mm = r.integers(-3, 4, 12).astype(np.int32)
+    t_agg = r.integers(-3, 4, 12).astype(np.int32)
+    one = np.ones(n, dtype=np.float32)
+    assert np.array_equal(
+        orc.gcn_hidden_layer_norm(rp, col, v, w, t_mm, one, one, t_agg.astype(np.float32)),
+        orc.gcn_hidden_layer(rp, col, v, w, t_mm, t_agg))
+    n, k = 64, 4
+    src = np.repeat(np.arange(n), k).astype(np.int32)
+    dst = ((src + np.tile(np.arange(1, k + 1), n)) % n).astype(np.int32)
+    rp, col = orc.adjacency(src, dst, n, W.ADJ_SYMMETRIZE)
+    assert np.all(orc.degrees(rp) == 2 * k)
+    v, w = W.pm1(r, (n, 10)), W.pm1(r, (20, 6))
+    tau = np.array([-0.5, -0.25, 0.0, 0.125, 0.25, 0.5, -0.75, 0.75, 0.375, -0.125], np.float32)
+    t_int = np.ceil(tau.astype(np.float64) * 2 * k).astype(np.int32)
+    t_mm = r.integers(-2, 3, 6).astype(np.int32)
+    rmean = np.full(n, 1.0 / (2 * k), dtype=np.float32)
+    assert np.array_equal(orc.sage_hidden_layer_mean(rp, col, v, w, rmean, tau, t_mm),
+                          orc.sage_hidden_layer(rp, col, v, w, t_int, t_mm))
