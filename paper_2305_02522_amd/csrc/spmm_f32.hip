@@ -11,9 +11,9 @@
 // decides an output bit.
 //
 // One wavefront per row (rows by decreasing degree, so the long ones start first), lanes
-// across channels: a neighbour's row is read as whole 256-byte segments.  The column ids
-// and factors of 64 neighbours are fetched with one load each and handed out by lane
-// reads.  The kernel is bound by the gather traffic, nnz * 4 C bytes for float
+// across channels: a neighbour's float row is read as whole 256-byte segments.  The column
+// ids and factors of 64 neighbours (and, for bit rows, their words) are fetched with one
+// load each and handed out by lane reads.  The kernel is bound by the gather traffic, nnz * 4 C bytes for float
 // activations: this is the price of full-precision aggregation that the bit path avoids.
 #include "common.h"
 
@@ -63,6 +63,36 @@ __global__ __launch_bounds__(256) void spmm_f32_kernel(
             const uint32_t cnt = end - k0 < 64u ? end - k0 : 64u;
             const uint32_t jl = (uint32_t)col[k0 + (lane < cnt ? lane : cnt - 1)];
             const float fl = f ? f[jl] : 1.0f;
+            if (XBITS) {
+                // Bit rows: every lane fetches the words of its own neighbour (one gather
+                // per tile for 64 neighbours); a neighbour's word is then read from its
+                // lane and, being the same for all lanes, serves as a lane mask.
+                uint32_t wlo[kTiles], whi[kTiles];
+#pragma unroll
+                for (int u = 0; u < kTiles; ++u) {
+                    uint64_t w = 0;
+                    if (c0 + 64 * u < C) // wave-uniform
+                        w = xb[(int64_t)jl * ldx + (c0 / 64 + u)];
+                    wlo[u] = (uint32_t)w;
+                    whi[u] = (uint32_t)(w >> 32);
+                }
+                for (uint32_t t = 0; t < cnt; ++t) {
+                    const float fj =
+                        __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fl), (int)t));
+#pragma unroll
+                    for (int u = 0; u < kTiles; ++u) {
+                        if (c0 + 64 * u >= C)
+                            continue;
+                        const uint64_t word =
+                            (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)wlo[u], (int)t) |
+                            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)whi[u], (int)t)
+                             << 32);
+                        const float x = __builtin_amdgcn_inverse_ballot_w64(word) ? 1.0f : -1.0f;
+                        acc[u] = acc[u] + mul_rounded(fj, x);
+                    }
+                }
+                continue;
+            }
             // kAhead neighbours per turn: their rows are requested together, then added in
             // order (a turn past the end repeats the last neighbour and drops it)
             for (uint32_t t = 0; t < cnt; t += kAhead) {
@@ -76,9 +106,6 @@ __global__ __launch_bounds__(256) void spmm_f32_kernel(
                     for (int u = 0; u < kTiles; ++u) {
                         if (c0 + 64 * u >= C) { // wave-uniform: tile beyond the last channel
                             xq[q][u] = 0.0f;
-                        } else if (XBITS) {
-                            const uint64_t word = xb[(int64_t)j * ldx + (c0 / 64 + u)];
-                            xq[q][u] = ((word >> lane) & 1ull) ? 1.0f : -1.0f;
                         } else {
                             xq[q][u] = xf[(int64_t)j * ldx + cc[u]];
                         }
