@@ -145,6 +145,17 @@ int bitgnn_adj_blocked_info(const bitgnn_adj *adj, int64_t *parts, int64_t *slic
                             int64_t *cb_nodes);
 void bitgnn_adj_destroy(bitgnn_adj *adj);
 
+/* Tuning utility (the paper's Section 3.4, per graph): runs bitgnn_bspmm's two kernels
+ * (CSR with global-memory gathers, column-blocked with LDS-staged gathers) `reps` times
+ * each on this graph for C channels, on scratch activations the call allocates and frees,
+ * and records the faster one in the handle: later bit aggregations of the same number of
+ * 128-channel passes take it instead of asking the built-in time model.  Results never
+ * depend on the choice.  csr_ms / blocked_ms (host pointers, may be NULL) receive the
+ * average time of a call in milliseconds, -1 for a form the handle does not have.
+ * Synchronises the stream.  The handle must not be in use by other calls meanwhile. */
+int bitgnn_adj_tune(bitgnn_ctx *ctx, void *stream, bitgnn_adj *adj, int32_t C, int32_t reps,
+                    float *csr_ms, float *blocked_ms);
+
 /* ---- BMM: XNOR-popcount product (Section 2.2, +-1 bit-dot-product) ------- */
 
 /* Z[i][c] = sum_k vx[i][k]*vw[k][c] = K - 2*popc(xbits_i xor wbits_c), where the

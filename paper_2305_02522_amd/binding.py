@@ -63,6 +63,7 @@ _SIGNATURES = {
                                 _vp, _vp, _i64]),
     "bitgnn_gcn_layer_f32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _i32, _i64, _vp, _vp,
                                     _vp, _vp, _i64]),
+    "bitgnn_adj_tune": (_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "bitgnn_bspmm": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
     "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
     "bitgnn_spmm_f32": (_int, [_vp, _vp, _vp, _vp, _int, _i32, _i64, _vp, _vp, _int, _vp, _vp,
@@ -244,6 +245,14 @@ def spmm_i32(ctx: Context, adj: Optional[Adjacency], Z, M, z_stride, z_abs_bound
              out_stride):
     ctx.check(_lib.bitgnn_spmm_i32(ctx.handle, _stream(), adj.handle if adj else None, _ptr(Z), M,
                                    z_stride, z_abs_bound, _ptr(alpha), _ptr(out), out_stride))
+
+
+def adj_tune(ctx: Context, adj: Optional[Adjacency], C: int, reps: int = 5):
+    """Times both aggregation kernels on this graph; returns (csr_ms, blocked_ms)."""
+    a, b = ctypes.c_float(-1.0), ctypes.c_float(-1.0)
+    ctx.check(_lib.bitgnn_adj_tune(ctx.handle, _stream(), adj.handle if adj else None, C, reps,
+                                   ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def spmm_f32(ctx: Context, adj: Optional[Adjacency], x, x_is_bits, C, ldx, r, f, epilogue, tau,

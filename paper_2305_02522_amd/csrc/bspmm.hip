@@ -1110,11 +1110,21 @@ bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
     return blk < csr;
 }
 
-int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint64_t *hbits,
-                    int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
-                    int64_t out_stride)
+// force: 0 = choose (a measured preference of bitgnn_adj_tune first, else the time model),
+// 1 = CSR kernel, 2 = column-blocked kernel (the caller has checked that the form exists)
+static int launch_bspmm_path(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                             const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
+                             const int32_t *T, void *out, int64_t out_stride, int force)
 {
-    if (bg_prefer_blocked(adj, (C + 127) / 128, 4 * (int64_t)((C + 31) / 32), 0.06))
+    const int passes = (C + 127) / 128;
+    bool blocked;
+    if (force)
+        blocked = force == 2;
+    else if (adj->blk && !adj->blk->forced && adj->pref[passes < 4 ? passes - 1 : 3])
+        blocked = adj->pref[passes < 4 ? passes - 1 : 3] == 2;
+    else
+        blocked = bg_prefer_blocked(adj, passes, 4 * (int64_t)((C + 31) / 32), 0.06);
+    if (blocked)
         return bg_launch_bspmm_blocked(ctx, s, adj, hbits, C, h_stride, epilogue, T, out,
                                        out_stride);
     const int32_t W32 = (C + 31) / 32;
@@ -1162,6 +1172,91 @@ int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const
     }
     bg_time_end(ctx, s);
     BG_LAUNCH_CHECK(ctx, "bitgnn_bspmm");
+    return BITGNN_OK;
+}
+
+int bg_launch_bspmm(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint64_t *hbits,
+                    int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
+                    int64_t out_stride)
+{
+    return launch_bspmm_path(ctx, s, adj, hbits, C, h_stride, epilogue, T, out, out_stride, 0);
+}
+
+namespace {
+struct TuneBuf { // device scratch of the tuning run, released on every return path
+    void *p = nullptr;
+    ~TuneBuf()
+    {
+        if (p)
+            (void)hipFree(p);
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 8); }
+};
+} // namespace
+
+// Tuning utility (Section 3.4): times the two aggregation kernels on this graph for a given
+// width and keeps the winner in the handle.
+extern "C" int bitgnn_adj_tune(bitgnn_ctx *ctx, void *stream, bitgnn_adj *adj, int32_t C,
+                               int32_t reps, float *csr_ms, float *blocked_ms)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_adj_tune: adj is null");
+    BG_REQUIRE(ctx, C >= 1 && reps >= 1 && reps <= 1000, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_adj_tune: C=%d reps=%d (1..1000)", C, reps);
+    BG_NEED_DEVICE(ctx);
+    if (csr_ms)
+        *csr_ms = -1.0f;
+    if (blocked_ms)
+        *blocked_ms = -1.0f;
+    if (adj->n == 0 || adj->nnz == 0)
+        return BITGNN_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t cw = ((int64_t)C + 63) / 64;
+    TuneBuf h, out, T;
+    BG_HIP(ctx, h.alloc((size_t)adj->n * cw * 8));
+    BG_HIP(ctx, out.alloc((size_t)adj->n * cw * 8));
+    BG_HIP(ctx, T.alloc((size_t)C * 4));
+    BG_HIP(ctx, hipMemsetAsync(h.p, 0x5A, (size_t)adj->n * cw * 8, s));
+    BG_HIP(ctx, hipMemsetAsync(T.p, 0, (size_t)C * 4, s));
+    hipEvent_t e0, e1;
+    BG_HIP(ctx, hipEventCreate(&e0));
+    BG_HIP(ctx, hipEventCreate(&e1));
+    float ms[3] = {0.0f, -1.0f, -1.0f};
+    int rc = BITGNN_OK;
+    for (int path = 1; path <= 2 && rc == BITGNN_OK; ++path) {
+        if (path == 2 && !adj->blk)
+            break;
+        // one untimed call first (workspace growth, code upload)
+        for (int i = 0; i <= reps && rc == BITGNN_OK; ++i) {
+            if (i == 1)
+                (void)hipEventRecord(e0, s);
+            rc = launch_bspmm_path(ctx, s, adj, (const uint64_t *)h.p, C, cw, BITGNN_EPI_THRESH_BITS,
+                                   (const int32_t *)T.p, out.p, cw, path);
+        }
+        if (rc != BITGNN_OK)
+            break;
+        (void)hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) {
+            rc = bitgnn_fail(ctx, BITGNN_ERR_HIP, "bitgnn_adj_tune: event synchronize failed");
+            break;
+        }
+        (void)hipEventElapsedTime(&ms[path], e0, e1);
+        ms[path] /= (float)reps;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipStreamSynchronize(s);
+    if (rc != BITGNN_OK)
+        return rc;
+    if (csr_ms)
+        *csr_ms = ms[1];
+    if (blocked_ms)
+        *blocked_ms = ms[2];
+    if (adj->blk) {
+        const int passes = (C + 127) / 128;
+        adj->pref[passes < 4 ? passes - 1 : 3] = ms[2] < ms[1] ? 2 : 1;
+    }
     return BITGNN_OK;
 }
 

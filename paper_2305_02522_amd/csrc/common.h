@@ -98,6 +98,9 @@ struct bitgnn_adj {
                        // gathers from a degree-ordered copy keep the hubs' rows together)
     size_t device_bytes;
     bitgnn_blocked *blk; // null when the graph is too sparse for the blocked path
+    // bitgnn_adj_tune's verdict for bit aggregations of 1, 2, 3, >= 4 passes of 128 channels:
+    // 0 = not measured (the time model decides), 1 = CSR kernel, 2 = column-blocked kernel
+    int8_t pref[4];
 };
 
 static inline int bitgnn_fail(bitgnn_ctx *ctx, int code, const char *fmt, ...)

@@ -82,6 +82,7 @@ def test_bgemm_validation(vctx):
 def test_aggregation_and_layer_validation(vctx):
     assert _code(B.bspmm, vctx, None, P8, 64, 1, B.EPI_THRESH_BITS, P8, P8, 1) == B.ERR_INVALID_ARG
     assert _code(B.spmm_i32, vctx, None, P8, 7, 7, 64, None, P8, 7) == B.ERR_INVALID_ARG
+    assert _code(B.adj_tune, vctx, None, 128, 3) == B.ERR_INVALID_ARG
     assert _code(B.spmm_f32, vctx, None, P8, 0, 7, 7, None, None, B.EPI_SCALE_F32, None, P8,
                  7) == B.ERR_INVALID_ARG
     assert _code(B.gcn_layer, vctx, None, P8, 2, 100, 2, P8, 64, 2, P8, P8, P8, P8, 1) == \

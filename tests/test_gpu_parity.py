@@ -342,6 +342,34 @@ def test_bspmm_star_graph_long_row(B, ctx, tuned):
     adj.close()
 
 
+def test_adj_tune_measures_both_kernels_and_keeps_results(B, ctx):
+    """The tuning utility times both aggregation kernels and records a preference; the
+    aggregation gives the same bits before and after, whichever kernel won."""
+    adj, rp, col, r = _graph(B, ctx, 20000, 400000, SYM_LOOPS, 77)
+    assert adj.blocked_info()["parts"] > 0
+    C = 128
+    v = W.pm1(r, (20000, C))
+    t = r.integers(-4, 5, size=C).astype(np.int32)
+    want = orc.to_words(orc.rebin(orc.spmm_pm1(rp, col, v), t))
+    hb = _pack_host(v)
+    for step in range(2):
+        ob = torch.zeros((20000, 2), dtype=torch.int64, device="cuda")
+        B.bspmm(ctx, adj, hb, C, 2, B.EPI_THRESH_BITS, dev(t), ob, 2)
+        torch.cuda.synchronize()
+        assert np.array_equal(words_np(ob), want)
+        if step == 0:
+            csr_ms, blk_ms = B.adj_tune(ctx, adj, C, 3)
+            assert csr_ms > 0 and blk_ms > 0
+    with pytest.raises(B.BitgnnError) as ex:
+        B.adj_tune(ctx, adj, 0, 3)
+    assert ex.value.code == B.ERR_INVALID_ARG
+    adj.close()
+    sparse, _, _, _ = _graph(B, ctx, 3000, 6000, SYM_LOOPS, 78)     # CSR only: nothing to choose
+    csr_ms, blk_ms = B.adj_tune(ctx, sparse, 64, 2)
+    assert csr_ms > 0 and blk_ms == -1.0
+    sparse.close()
+
+
 # ------------------------------------------------------------------ a5: integer aggregation
 @pytest.mark.parametrize("n,e,M", [(50, 200, 1), (1000, 9000, 7), (3000, 50000, 41),
                                    (500, 4000, 64), (300, 2000, 130)])
