@@ -283,6 +283,15 @@ int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *
                                int64_t w_stride, const float *r, const float *f,
                                const float *tau_agg, const int32_t *T_mm, uint64_t *out_bits,
                                int64_t out_stride);
+/* GCN output layer with the weighted adjacency:
+ *   logits = r .* (A_hat (f .* (alpha .* (xbits W)))),
+ * BMM.BBF with its scale, then the full-precision weighted aggregation.
+ * tmp_f32: caller scratch float [N][M].  Other arguments as in bitgnn_gcn_out_layer. */
+int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                  const uint64_t *xbits, int64_t x_stride, int32_t K,
+                                  int32_t kwords, const uint64_t *wbits, int32_t M,
+                                  int64_t w_stride, const float *alpha, const float *r,
+                                  const float *f, float *tmp_f32, float *logits, int64_t ldo);
 
 #ifdef __cplusplus
 }

@@ -268,6 +268,17 @@ def gcn_hidden_layer_norm(rowptr, col, v, w, t_mm, r, f, tau_agg) -> np.ndarray:
     return rebin_f32(spmm_weighted_f32(rowptr, col, h, r, f), tau_agg)
 
 
+def gcn_out_layer_norm(rowptr, col, v, w, alpha, r, f) -> np.ndarray:
+    """Z = v W (integers);  logits = diag(r) A_hat diag(f) (alpha * Z): the output layer with
+    a weighted adjacency; BMM.BBF with its scale, then the full-precision weighted
+    aggregation (float32, step by step)."""
+    n = v.shape[0]
+    z = np.empty((n, w.shape[1]), dtype=np.float32)
+    for lo in range(0, n, _CHUNK):
+        z[lo:lo + _CHUNK] = scale(bmm(v[lo:lo + _CHUNK], w), alpha)
+    return spmm_weighted_f32(rowptr, col, z, r, f)
+
+
 def sage_hidden_layer_mean(rowptr, col, v, w, rmean, tau_agg, t_mm) -> np.ndarray:
     """nb = bin_{tau}(mean_{j in N(i)} v_j) with rmean = 1/deg (the mean aggregator of
     Section 2.1);  out = bin_{t_mm}([v | nb] W)."""

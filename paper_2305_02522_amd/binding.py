@@ -77,6 +77,8 @@ _SIGNATURES = {
                                      _i64]),
     "bitgnn_gcn_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64,
                                          _vp, _vp, _vp, _vp, _vp, _vp, _i64]),
+    "bitgnn_gcn_out_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64,
+                                             _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_sage_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp,
                                           _vp, _vp, _vp, _i64]),
 }
@@ -283,6 +285,14 @@ def gcn_layer_weighted(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, 
         ctx.handle, _stream(), adj.handle if adj else None, _ptr(xbits), x_stride, K, kwords,
         _ptr(wbits), M, w_stride, _ptr(T_mm), _ptr(r), _ptr(f), _ptr(tau_agg), _ptr(tmp_bits),
         _ptr(out_bits), out_stride))
+
+
+def gcn_out_layer_weighted(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride,
+                           alpha, r, f, tmp_f32, logits, ldo):
+    ctx.check(_lib.bitgnn_gcn_out_layer_weighted(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(xbits), x_stride, K, kwords,
+        _ptr(wbits), M, w_stride, _ptr(alpha), _ptr(r), _ptr(f), _ptr(tmp_f32), _ptr(logits),
+        ldo))
 
 
 def sage_layer_weighted(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, r, f, tau_agg,

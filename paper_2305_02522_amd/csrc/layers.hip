@@ -229,3 +229,35 @@ extern "C" int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const b
     return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
                            BITGNN_EPI_THRESH_BITS, T_mm, nullptr, out_bits, out_stride);
 }
+
+// Output layer with a weighted adjacency: logits = diag(r) A_hat diag(f) (alpha .* (xbits W)).
+// BMM.BBF with its scale writes float rows into the caller's scratch, the full-precision
+// weighted aggregation follows (BSpMM with a float activation operand and float output).
+extern "C" int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                             const uint64_t *xbits, int64_t x_stride, int32_t K,
+                                             int32_t kwords, const uint64_t *wbits, int32_t M,
+                                             int64_t w_stride, const float *alpha, const float *r,
+                                             const float *f, float *tmp_f32, float *logits,
+                                             int64_t ldo)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_out_layer_weighted: adj is null");
+    const int64_t n = adj->n;
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                            BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_spmm_f32(ctx, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_SCALE_F32, nullptr, logits,
+                           ldo);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                         BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_spmm_f32(ctx, s, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_SCALE_F32, nullptr,
+                              logits, ldo);
+}

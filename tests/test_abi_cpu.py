@@ -92,6 +92,8 @@ def test_aggregation_and_layer_validation(vctx):
     assert _code(B.sage_layer, vctx, None, P8, 100, P8, 64, 4, P8, P8, P8, 2) == B.ERR_INVALID_ARG
     assert _code(B.sage_layer_weighted, vctx, None, P8, 100, P8, 64, 4, P8, None, P8, P8, P8,
                  2) == B.ERR_INVALID_ARG
+    assert _code(B.gcn_out_layer_weighted, vctx, None, P8, 2, 100, 2, P8, 7, 2, P8, P8, P8, P8,
+                 P8, 7) == B.ERR_INVALID_ARG
     assert _code(B.gcn_layer_weighted, vctx, None, P8, 2, 100, 2, P8, 64, 2, P8, P8, P8, P8, P8,
                  P8, 1) == B.ERR_INVALID_ARG
     assert _code(B.sage_out_layer, vctx, None, P8, 100, P8, 7, 4, P8, P8, P8, 7) == \

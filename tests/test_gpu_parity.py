@@ -591,6 +591,23 @@ def test_weighted_layers(B, ctx, n, e, K, M):
     torch.cuda.synchronize()
     want2 = orc.sage_hidden_layer_mean(rp, col, v, w2, mean, tau_k, t_mm)
     assert np.array_equal(words_np(out2), orc.to_words(want2))
+    # normalised 2-layer GCN end to end: hidden layer above, then the weighted output layer
+    classes = 7
+    w3 = W.pm1(r, (M, classes))
+    alpha = r.uniform(0.5, 1.5, classes).astype(np.float32)
+    tmpf = torch.zeros((n, classes), dtype=torch.float32, device="cuda")
+    logits = torch.zeros((n, classes), dtype=torch.float32, device="cuda")
+    B.gcn_out_layer_weighted(ctx, adj, out, mw, M, mw, _pack_host(np.ascontiguousarray(w3.T)),
+                             classes, mw, dev(alpha), dev(dinv), dev(dinv), tmpf, logits, classes)
+    torch.cuda.synchronize()
+    want3 = orc.gcn_out_layer_norm(rp, col, want, w3, alpha, dinv, dinv)
+    got3 = logits.cpu().numpy()
+    # same steps on both sides; a last-bit difference in alpha * Z would still stay within
+    # the rounding bound of the sum, (deg + 4) * 2^-23 * sum|terms|
+    zabs = np.abs(orc.scale(orc.bmm(want, w3), alpha)).astype(np.float64)
+    mag = orc.spmm_weighted(rp, col, zabs, dinv, dinv)
+    assert np.all(np.abs(got3.astype(np.float64) - want3) <=
+                  (orc.degrees(rp)[:, None] + 4) * 2.0 ** -23 * mag + 1e-30)
     adj.close()
 
 

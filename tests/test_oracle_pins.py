@@ -471,3 +471,15 @@ def test_weighted_layers_reduce_to_the_integer_layers():
     rmean = np.full(n, 1.0 / (2 * k), dtype=np.float32)
     assert np.array_equal(orc.sage_hidden_layer_mean(rp, col, v, w, rmean, tau, t_mm),
                           orc.sage_hidden_layer(rp, col, v, w, t_int, t_mm))
+
+
+def test_weighted_out_layer_reduces_to_the_integer_out_layer():
+    """Unit factors, alpha = 1: the weighted output layer gives the integers of the exact
+    output layer (small enough to be exact in float32)."""
+    r, n, rp, col = _small_graph(12, n=70, e=500)
+    v, w = W.pm1(r, (n, 24)), W.pm1(r, (24, 5))
+    one = np.ones(5, dtype=np.float32)
+    got = orc.gcn_out_layer_norm(rp, col, v, w, one, None, None)
+    assert np.array_equal(got, orc.gcn_out_layer(rp, col, v, w, one))
+    y64 = orc.spmm_weighted(rp, col, orc.bmm(v, w).astype(np.float64))
+    assert np.array_equal(got.astype(np.float64), y64)
