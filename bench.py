@@ -8,7 +8,11 @@ and the prebuilt adjacency already resident in HBM.  The adjacency build and the
 weight packing are done once before the timed region (they are offline steps in
 the paper) and their time is reported separately.
 
-Prints ONE JSON line (see the design doc for the definition of every field).
+Prints ONE JSON line: `value` = bit operations of a step (N K M per BMM, nnz C per
+aggregation) / step time; `kernels` = per library call, from HIP events on the launch
+stream; `roofline` = the dominant kernel's algorithmic bytes / its own launch time against
+the HBM peak, with the HBM traffic the profiler's counters report; `cpu_baseline` = the CPU
+oracle timed on the host cores on the same workload.
 """
 from __future__ import annotations
 
