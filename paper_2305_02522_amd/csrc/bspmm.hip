@@ -408,6 +408,13 @@ __device__ __forceinline__ blk_item blk_item_of(uint2 it, uint4 d, uint32_t slic
     return r;
 }
 
+// A workgroup barrier that orders LDS accesses only (no wait for global loads or stores in
+// flight).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Launched with one workgroup per compute unit (its LDS block leaves room for one
 // only).  Every workgroup takes work items (kSlicesPerWg slices each, heaviest first)
 // from an atomic counter until the list is exhausted: a compute unit that finishes
@@ -427,6 +434,9 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     __shared__ uint32_t s_next;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the block buffer (without its zero rows) can stage every wavefront's partial planes,
+    // 64 x 8 x 16 bytes each
+    const bool stage_ok = cbn >= (uint32_t)kSlicesPerWg * 64u * 8u;
     if (tid < 16)
         hblk[cbn + tid] = make_uint4(0u, 0u, 0u, 0u);
     if (tid == 0)
@@ -565,9 +575,28 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
                 carry = nc;
             }
         }
-        // partial planes are filed under the part id, so that the merge reads the parts of
-        // a row, and of consecutive rows, back to back
-        if (writes) {
+        // Partial planes are filed under the part id, so that the merge reads the parts of
+        // a row, and of consecutive rows, back to back.  A lane storing its own 8 planes
+        // would touch 64 different 128-byte lines with every store instruction; instead the
+        // wavefront turns its 64 x 8 planes around in LDS (the block buffer is free once
+        // everyone is done gathering) so that 8 adjacent lanes store one part's whole line.
+        if (PP == 8 && stage_ok) {
+            lds_barrier();
+            uint4 *stage = hblk + (uint32_t)wave * (64 * PP);
+#pragma unroll
+            for (int p = 0; p < PP; ++p)
+                stage[lane * PP + p] = make_uint4(acc[p][0], acc[p][1], acc[p][2], acc[p][3]);
+            // (a wavefront reads back only what it wrote itself: no barrier)
+#pragma unroll 1
+            for (int r = 0; r < 64 * PP / 64; ++r) {
+                const int src = r * (64 / PP) + lane / PP; // the part whose line this lane helps store
+                const uint4 v = stage[src * PP + lane % PP];
+                const uint32_t svid = (uint32_t)__shfl((int)vid, src, 64);
+                const int swr = __shfl((int)writes, src, 64);
+                if (swr)
+                    partial[(uint64_t)svid * PP + lane % PP] = v;
+            }
+        } else if (writes) {
 #pragma unroll
             for (int p = 0; p < PP; ++p)
                 partial[(uint64_t)vid * PP + p] =
