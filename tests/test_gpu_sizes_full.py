@@ -113,6 +113,39 @@ def test_cfg4_logits():
     _run(4).check_layer(1)
 
 
+def test_cfg4_weighted_aggregation_sampled_rows():
+    """The symmetric-normalised aggregation at full size (what `bench.py --op spmm_f32`
+    times: float rows and bit rows, C = the first hidden width), on sampled output rows the
+    oracle computes one by one: the hub rows, the lowest-degree rows and a random sample."""
+    from paper_2305_02522_amd import binding as B
+    r = _run(4)
+    n, C = r.wl.n, int(r.wl.dims[1])
+    deg = orc.degrees(r.rp)
+    dinv = (np.maximum(deg, 1).astype(np.float64) ** -0.5).astype(np.float32)
+    rng = np.random.default_rng(5)
+    xf = rng.standard_normal((n, C)).astype(np.float32)
+    v = W.pm1(rng, (n, C))
+    order = np.argsort(-deg, kind="stable")
+    rows = np.unique(np.concatenate([order[:8], order[-64:], rng.integers(0, n, 600)]))
+    tau = rng.uniform(-0.2, 0.2, C).astype(np.float32)
+    cw = (C + 63) // 64
+    for bits, xh in ((0, xf), (1, v.astype(np.float32))):
+        xd = dev(orc.to_words(v).view(np.int64)) if bits else dev(xf)
+        out = torch.empty((n, C), dtype=torch.float32, device="cuda")
+        ob = torch.empty((n, cw), dtype=torch.int64, device="cuda")
+        B.spmm_f32(r.ctx, r.adj, xd, bits, C, cw if bits else C, dev(dinv), dev(dinv),
+                   B.EPI_SCALE_F32, None, out, C)
+        B.spmm_f32(r.ctx, r.adj, xd, bits, C, cw if bits else C, dev(dinv), dev(dinv),
+                   B.EPI_THRESH_BITS, dev(tau), ob, cw)
+        torch.cuda.synchronize()
+        got, gotb = out.cpu().numpy(), words_np(ob)
+        for i in rows:
+            want = orc.spmm_weighted_f32(r.rp, r.col, xh, dinv, dinv, rows=(int(i), int(i) + 1))
+            assert np.array_equal(got[i:i + 1], want), f"row {i} (degree {deg[i]}) bits={bits}"
+            assert np.array_equal(gotb[i:i + 1], orc.to_words(orc.rebin_f32(want, tau)))
+    say(f"cfg4: weighted aggregation checked on {len(rows)} rows, degrees up to {deg[rows].max()}")
+
+
 def test_cfg5_adjacency_and_layer0():
     r = _run(5)
     assert r.adj.nnz == r.rp[-1]
