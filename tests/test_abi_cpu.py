@@ -103,3 +103,13 @@ def test_aggregation_and_layer_validation(vctx):
 def test_ctx_create_rejects_bad_device():
     with pytest.raises(B.BitgnnError):
         B.Context(-2)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only and says so before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
