@@ -264,7 +264,6 @@ __global__ void csr_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_s
 // Counter planes of a row part: 8 when parts have at most 255 entries (the partial
 // planes of a part are then exactly one 128-byte line), else 10 (up to 1023 entries).
 static int part_planes_for(const bitgnn_blocked *b) { return b->part_len <= 255 ? 8 : 10; }
-constexpr int kBlkThreads = 64 * kSlicesPerWg;
 
 constexpr int kPendLow = 3; // a block of 8 gathers produces one carry of weight 2^3
 constexpr int kPendTop = 6; // levels 3..5 park a carry; above, carries ripple (rare)
@@ -423,8 +422,9 @@ __device__ __forceinline__ void lds_barrier()
 // while the last block of the current one is processed (late enough to go to whichever
 // workgroup is about to be free), and its descriptors and first ids are requested
 // step by step behind the barriers of that block, so the switch costs no round trip.
-template <int PP>
-__global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
+// SPW: slices (wavefronts) per work item and workgroup.
+template <int PP, int SPW>
+__global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint2 *__restrict__ wg_item,
     const uint4 *__restrict__ sl_desc, const uint32_t *__restrict__ tile_group,
     const uint32_t *__restrict__ idx, const uint32_t *__restrict__ part_vid, uint32_t S,
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the block buffer (without its zero rows) can stage every wavefront's partial planes,
     // 64 x 8 x 16 bytes each
-    const bool stage_ok = cbn >= (uint32_t)kSlicesPerWg * 64u * 8u;
+    const bool stage_ok = cbn >= (uint32_t)SPW * 64u * 8u;
     if (tid < 16)
         hblk[cbn + tid] = make_uint4(0u, 0u, 0u, 0u);
     if (tid == 0)
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
     blk_item it;
     {
         const uint2 w = wg_item[cur];
-        const uint32_t slice = w.x * kSlicesPerWg + wave;
+        const uint32_t slice = w.x * SPW + wave;
         const bool has = slice < S;
         it = blk_item_of(w, sl_desc[has ? slice : 0u], slice, has);
     }
@@ -504,8 +504,8 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             // A wavefront copies 64 consecutive rows per instruction, straight from L2 into
             // LDS (no register round trip); the ragged end of the last block goes row by row.
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const uint32_t w0 = (uint32_t)wave * 64u + (uint32_t)k * kBlkThreads; // uniform
+            for (int k = 0; k < 8 * (kSlicesPerWg / SPW); ++k) {
+                const uint32_t w0 = (uint32_t)wave * 64u + (uint32_t)k * (64u * SPW); // uniform
                 if (w0 + 64u <= rows) {
                     __builtin_amdgcn_global_load_lds(
                         (const __attribute__((address_space(1))) void *)(hperm + base + w0 + lane),
@@ -520,7 +520,7 @@ __global__ __launch_bounds__(kBlkThreads) void bspmm_blk_kernel(
             { const long long t = BLK_PROF_T(); p_fill += t - p_t0; p_t0 = t; }
 #endif
             if (last) { // second descriptor of the next item
-                nslice = nw.x * kSlicesPerWg + wave;
+                nslice = nw.x * SPW + wave;
                 nhas = nslice < S;
                 nd = sl_desc[nhas ? nslice : 0u];
             }
@@ -924,21 +924,31 @@ static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, con
     const size_t lds = ((size_t)b->cbn + 16) * 16;
     const uint32_t cus = ctx->n_cus > 0 ? (uint32_t)ctx->n_cus : 256u;
     const unsigned grid = b->n_wgs < cus ? b->n_wgs : cus;
-#define BG_BLK(PPV)                                                                               \
+#define BG_BLK(PPV, SPWV)                                                                         \
     do {                                                                                          \
-        BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel<PPV>,                      \
+        BG_HIP(ctx, hipFuncSetAttribute((const void *)bspmm_blk_kernel<PPV, SPWV>,                \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));   \
         bg_time_begin(ctx, s);                                                                    \
-        bspmm_blk_kernel<PPV><<<grid, kBlkThreads, lds, s>>>(                                     \
+        bspmm_blk_kernel<PPV, SPWV><<<grid, 64 * SPWV, lds, s>>>(                                 \
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_item, b->sl_desc, b->tile_group,     \
             (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, b->n_wgs,           \
             ctx->queue, partial);                                                                 \
         bg_time_end(ctx, s);                                                                      \
     } while (0)
+#define BG_BLK_SPW(PPV)                                                                           \
+    do {                                                                                          \
+        if (b->spw == 16)                                                                         \
+            BG_BLK(PPV, 16);                                                                      \
+        else if (b->spw == 8)                                                                     \
+            BG_BLK(PPV, 8);                                                                       \
+        else                                                                                      \
+            BG_BLK(PPV, 4);                                                                       \
+    } while (0)
     if (part_planes_for(b) == 8)
-        BG_BLK(8);
+        BG_BLK_SPW(8);
     else
-        BG_BLK(10);
+        BG_BLK_SPW(10);
+#undef BG_BLK_SPW
 #undef BG_BLK
     BG_LAUNCH_CHECK(ctx, "bspmm_blk");
     return BITGNN_OK;

@@ -57,11 +57,9 @@ static inline void bg_time_end(bitgnn_ctx *ctx, hipStream_t s)
 static const int kGroupSteps = BITGNN_GROUP_STEPS;
 static_assert(kGroupSteps == 8 || kGroupSteps == 16, "groups of 8 or 16 steps");
 
-// Slices (wavefronts) per workgroup of the blocked bit-SpMM.
-#ifndef BITGNN_SLICES_PER_WG
-#define BITGNN_SLICES_PER_WG 16
-#endif
-static const int kSlicesPerWg = BITGNN_SLICES_PER_WG;
+// Slices (wavefronts) per workgroup of the blocked bit-SpMM: 16 on large graphs; 8 or 4
+// where that is what it takes to give every compute unit a work item.
+static const int kSlicesPerWg = 16;
 
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {
@@ -71,7 +69,8 @@ struct bitgnn_blocked {
     int32_t forced;         // built with a density threshold of 0: always preferred
     uint32_t n_vrows;       // V: row parts ("virtual rows")
     uint32_t n_slices;      // ceil(V / 64)
-    uint32_t n_wgs;         // ceil(slices / kSlicesPerWg)
+    int32_t spw;            // slices (wavefronts) per work item: 16, 8 or 4
+    uint32_t n_wgs;         // ceil(slices / spw)
     uint32_t n_tiles;       // (slice, column block) tiles
     uint32_t n_groups;      // groups of kGroupSteps gather steps over all tiles
     uint2 *wg_item;         // [n_wgs] by decreasing estimated work: {workgroup,

@@ -294,7 +294,8 @@ def _graph(B, ctx, n, e, flags, seed, hubs=0):
     (3000, 40000, 100, W.ADJ_SYMMETRIZE, 0), (5000, 100000, 128, SYM_LOOPS, 2),
     (2000, 30000, 256, SYM_LOOPS, 0), (1500, 9000, 500, W.ADJ_SYMMETRIZE, 0),
     (40000, 100000, 128, SYM_LOOPS, 1), (700, 300, 65, 0, 0),
-    (70000, 200000, 96, SYM_LOOPS, 0)])      # CSR path with the degree-ordered gather table
+    (70000, 200000, 96, SYM_LOOPS, 0),       # CSR path with the degree-ordered gather table
+    (200000, 1000000, 64, SYM_LOOPS, 0)])    # blocked path with work items of 8 slices
 def test_bspmm_raw_and_threshold(B, ctx, tuned, n, e, C, flags, hubs):
     adj, rp, col, r = _graph(B, ctx, n, e, flags, n + C, hubs)
     v = W.pm1(r, (n, C))
