@@ -293,6 +293,42 @@ int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_ad
                                   int64_t w_stride, const float *alpha, const float *r,
                                   const float *f, float *tmp_f32, float *logits, int64_t ldo);
 
+/* ---- whole model in one launch (Section 3.3: the end-to-end fused kernel) - */
+
+/* Range of bitgnn_gcn2_fused (larger inputs are not launch-bound: use the layer calls). */
+#define BITGNN_FUSED_MAX_NODES 65536
+#define BITGNN_FUSED_MAX_DEGREE 1024
+#define BITGNN_FUSED_MAX_HIDDEN 256
+#define BITGNN_FUSED_MAX_CLASSES 64
+
+/* Two-layer GCN on float features in ONE kernel launch, for small graphs: the same
+ * result as bitgnn_gcn_layer_f32 (tau = NULL) followed by bitgnn_gcn_out_layer,
+ *   h  = (bin(x) W1 >= T_mm);  h1 = (A_hat h >= T_agg);  logits = alpha .* (A_hat (h1 W2)),
+ * with grid-wide barriers inside the kernel where those calls have kernel boundaries
+ * (the cooperative whole-model kernel of Section 3.3).  Integers and bits are exact, so
+ * the outputs are identical to the layer calls'.
+ * x: float [N][ldx], K0 features.  w1bits: uint64 [C1][w1_stride] (K0 bits per row),
+ * w2bits: uint64 [M][w2_stride] (C1 bits per row), pad bits zero (bitgnn_pack_weights_i8).
+ * T_mm, T_agg: int32 [C1].  alpha: float [M].
+ * tmp_bits: caller scratch uint64 [N][ceil(C1/64)] (dense) <- h.
+ * h_bits:   uint64 [N][h_stride] <- h1 (an output: ceil(C1/64) words per row, pad bits 0).
+ * logits:   float [N][ldo].
+ * status:   device int32 or NULL.  The kernel's waits are bounded (seconds); if one is
+ *           ever abandoned (the grid could not become resident: compute units taken away
+ *           from the process), the kernel adds 1 to *status, skips the remaining work and
+ *           exits; logits and h_bits are then undefined.  Never cleared by the library.
+ * Errors: BITGNN_ERR_RANGE beyond the limits above (N, largest degree, C1, M), with the
+ * limits in the message; BITGNN_ERR_INVALID_ARG / BITGNN_ERR_ALIGNMENT as elsewhere.
+ * One fused call at a time per context (the barrier counter lives in the context); it is
+ * asynchronous on `stream` like every other call.  All pointers are device pointers owned
+ * by the caller. */
+int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const float *x,
+                      int32_t K0, int64_t ldx, const uint64_t *w1bits, int32_t C1,
+                      int64_t w1_stride, const int32_t *T_mm, const int32_t *T_agg,
+                      const uint64_t *w2bits, int32_t M, int64_t w2_stride, const float *alpha,
+                      uint64_t *tmp_bits, uint64_t *h_bits, int64_t h_stride, float *logits,
+                      int64_t ldo, int32_t *status);
+
 #ifdef __cplusplus
 }
 #endif

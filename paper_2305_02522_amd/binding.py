@@ -81,6 +81,8 @@ _SIGNATURES = {
                                              _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_sage_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp,
                                           _vp, _vp, _vp, _i64]),
+    "bitgnn_gcn2_fused": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _i32, _i64, _vp, _vp, _vp,
+                                 _i32, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -316,6 +318,17 @@ def sage_out_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg,
                                          _ptr(T_agg), _ptr(alpha), _ptr(logits), ldo))
 
 
+FUSED_MAX_NODES, FUSED_MAX_DEGREE, FUSED_MAX_HIDDEN, FUSED_MAX_CLASSES = 65536, 1024, 256, 64
+
+
+def gcn2_fused(ctx: Context, adj, x, K0, ldx, w1bits, C1, w1_stride, T_mm, T_agg, w2bits, M,
+               w2_stride, alpha, tmp_bits, h_bits, h_stride, logits, ldo, status=None):
+    ctx.check(_lib.bitgnn_gcn2_fused(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(x), K0, ldx, _ptr(w1bits), C1,
+        w1_stride, _ptr(T_mm), _ptr(T_agg), _ptr(w2bits), M, w2_stride, _ptr(alpha),
+        _ptr(tmp_bits), _ptr(h_bits), h_stride, _ptr(logits), ldo, _ptr(status)))
+
+
 # --- model runner: buffers + the call sequence, no arithmetic ---------------
 
 class BinaryGNN:
@@ -355,6 +368,7 @@ class BinaryGNN:
             width = kw if model == "gcn" else 2 * kw
             self.act.append(torch.zeros((n, width), dtype=torch.int64, device=dev))
         m_last = dims[-1]
+        self.fused_status = None
         self.logits = torch.empty((n, m_last), dtype=torch.float32, device=dev)
         if model == "gcn":
             mw = max(words(d) for d in dims[1:-1]) if len(dims) > 2 else 1
@@ -400,6 +414,28 @@ class BinaryGNN:
                     nxt = self.act[l + 1]
                     sage_layer(ctx, adj, a, p["k_in"], p["wb"], p["m"], p["wb"].stride(0),
                                p["t_agg"], p["t_mm"], nxt, nxt.stride(0))
+        return self.logits
+
+    @property
+    def fused_applies(self) -> bool:
+        """Whether the model is a two-layer GCN inside the one-launch kernel's range."""
+        return (self.model == "gcn" and len(self.params) == 2
+                and self.n <= FUSED_MAX_NODES and self.adj.max_degree <= FUSED_MAX_DEGREE
+                and self.dims[1] <= FUSED_MAX_HIDDEN and self.dims[2] <= FUSED_MAX_CLASSES)
+
+    def forward_fused(self, x_f32: torch.Tensor) -> torch.Tensor:
+        """The whole model in one kernel launch (two-layer GCN on a small graph).  Same
+        buffers and results as forward(); `fused_status` counts abandoned barrier waits."""
+        n, k0 = x_f32.shape
+        assert n == self.n and k0 == self.dims[0]
+        p0, p1 = self.params
+        if self.fused_status is None:
+            self.fused_status = torch.zeros(1, dtype=torch.int32, device=self.logits.device)
+        h1 = self.act[1]
+        gcn2_fused(self.ctx, self.adj, x_f32, k0, x_f32.stride(0), p0["wb"], p0["m"],
+                   p0["wb"].stride(0), p0["t_mm"], p0["t_agg"], p1["wb"], p1["m"],
+                   p1["wb"].stride(0), p1["alpha"], self.tmp_bits, h1, h1.stride(0),
+                   self.logits, self.logits.stride(0), self.fused_status)
         return self.logits
 
     def forward_ops(self, x_f32: torch.Tensor, mark=None) -> torch.Tensor:

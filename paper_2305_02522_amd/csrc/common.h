@@ -16,7 +16,9 @@ struct bitgnn_ctx {
     int n_cus;            // compute units of the device
     int bgemm_path;       // 0: choose per shape, 1: VALU kernel, 2: matrix-core kernel
                           // (environment BITGNN_BGEMM=valu|mfma at context creation)
-    uint32_t *queue;      // device word: work counter of the blocked bit-SpMM
+    uint32_t *queue;      // device words: [0] work counter of the blocked bit-SpMM,
+                          // [kFusedBarrierWord] arrival counter of the fused kernel's barriers
+    uint32_t bar_base;    // value of that arrival counter once every launch so far has drained
     char err[256];
     uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
     size_t seed_table_words;
@@ -35,6 +37,7 @@ struct bitgnn_ctx {
 };
 
 static const int kMaxTimed = 256;
+static const int kFusedBarrierWord = 16; // its own 64-byte line of ctx->queue
 // Brackets one kernel launch with events when timing is on (no-ops otherwise).
 static inline void bg_time_begin(bitgnn_ctx *ctx, hipStream_t s)
 {

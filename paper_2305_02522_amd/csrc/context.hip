@@ -32,6 +32,8 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
         if (e == hipSuccess)
             e = hipMalloc((void **)&ctx->queue, 256);
         if (e == hipSuccess)
+            e = hipMemset(ctx->queue, 0, 256);
+        if (e == hipSuccess)
             e = hipMalloc((void **)&ctx->seed_table, kSeedTableWords * sizeof(uint32_t));
         if (e != hipSuccess) {
             free(ctx);

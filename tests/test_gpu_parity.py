@@ -625,6 +625,106 @@ def test_forward_ops_equals_forward(B, ctx):
         adj.close()
 
 
+# ------------------------------------------------------------------ whole model, one launch
+def _fused_case(B, ctx, n, e, dims, flags, seed, hubs=0, real_features=True):
+    """A two-layer GCN on a seeded graph through bitgnn_gcn2_fused and through the oracle."""
+    adj, rp, col, r = _graph(B, ctx, n, e, flags, seed, hubs)
+    layers = W.model_params(r, "gcn", list(dims))
+    if real_features:
+        x = r.standard_normal((n, dims[0])).astype(np.float32)
+        x[r.random((n, dims[0])) < 0.05] = 0.0          # exact zeros binarize to +1
+    else:
+        x = W.pm1(r, (n, dims[0]), 0.013).astype(np.float32)
+    model = B.BinaryGNN(ctx, "gcn", adj, list(dims), layers)
+    return adj, rp, col, layers, x, model
+
+
+def _check_fused(B, model, rp, col, layers, x):
+    xd = dev(x)
+    assert model.fused_applies
+    logits = model.forward_fused(xd)
+    torch.cuda.synchronize()
+    assert int(model.fused_status.item()) == 0, "a grid barrier wait was abandoned"
+    v0 = orc.bin_f32(x)
+    ref, hidden = orc.forward("gcn", rp, col, v0, layers, return_hidden=True)
+    c1 = hidden[0].shape[1]
+    mw = (c1 + 63) // 64
+    h = orc.rebin(orc.bmm(v0, layers[0].w), layers[0].t_mm)
+    assert np.array_equal(words_np(model.tmp_bits)[:, :mw], orc.to_words(h)), "BMM bits"
+    assert np.array_equal(words_np(model.act[1])[:, :mw], orc.to_words(hidden[0])), "hidden bits"
+    assert rel_close(logits.cpu().numpy(), ref), "logits"
+    return logits.clone(), model.act[1].clone()
+
+
+@pytest.mark.parametrize("n,e,dims,flags,hubs", [
+    (1, 0, (1, 1, 1), W.ADJ_ADD_SELF_LOOPS, 0),
+    (5, 6, (70, 64, 7), W.ADJ_SYMMETRIZE, 0),                  # isolated nodes: degree 0 rows
+    (300, 1500, (1433, 64, 7), SYM_LOOPS, 0),
+    (1000, 5000, (65, 65, 64), SYM_LOOPS, 0),                  # two tiles, ragged; 64 classes
+    (2000, 9000, (600, 128, 41), SYM_LOOPS, 1),                # a row of ~1000 neighbours
+    (4097, 30000, (129, 256, 10), SYM_LOOPS, 0),               # four tiles
+    (3000, 12000, (512, 200, 3), W.ADJ_SYMMETRIZE, 0),         # ragged four tiles
+    (20000, 90000, (500, 64, 3), SYM_LOOPS, 0)])               # several rows per wavefront
+def test_gcn2_fused_matches_oracle_and_layer_calls(B, ctx, n, e, dims, flags, hubs):
+    adj, rp, col, layers, x, model = _fused_case(B, ctx, n, e, dims, flags, 500 + n, hubs)
+    assert adj.max_degree <= B.FUSED_MAX_DEGREE
+    fused_logits, fused_h = _check_fused(B, model, rp, col, layers, x)
+    # the un-fused layer calls on the same buffers: identical bits and logits
+    model.act[1].zero_()
+    model.logits.zero_()
+    plain = model.forward(dev(x))
+    torch.cuda.synchronize()
+    assert torch.equal(model.act[1], fused_h)
+    assert torch.equal(plain, fused_logits)
+    # again, after other work went through the context: the barrier counter carries on
+    model.act[1].zero_()
+    model.logits.zero_()
+    again = model.forward_fused(dev(x))
+    torch.cuda.synchronize()
+    assert int(model.fused_status.item()) == 0
+    assert torch.equal(model.act[1], fused_h) and torch.equal(again, fused_logits)
+    adj.close()
+
+
+def test_gcn2_fused_config1_full_size(B, ctx):
+    wl = W.make_workload(1)
+    adj = B.adj_build(ctx, dev(wl.src), dev(wl.dst), len(wl.src), wl.n, wl.adj_flags)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    model = B.BinaryGNN(ctx, "gcn", adj, wl.dims, wl.layers)
+    _check_fused(B, model, rp, col, wl.layers, wl.x.astype(np.float32))
+    adj.close()
+
+
+def test_gcn2_fused_rejects_what_it_cannot_run(B, ctx):
+    """Outside its range the call fails before launching, naming the limits."""
+    adj, rp, col, layers, x, model = _fused_case(B, ctx, 3000, 9000, (64, 64, 7), SYM_LOOPS, 77,
+                                                 hubs=2)
+    assert adj.max_degree > B.FUSED_MAX_DEGREE and not model.fused_applies
+    with pytest.raises(B.BitgnnError) as e:
+        model.forward_fused(dev(x))
+    assert e.value.code == B.ERR_RANGE and "degree <= 1024" in str(e.value)
+    adj.close()
+    adj, rp, col, layers, x, model = _fused_case(B, ctx, 500, 2000, (64, 300, 7), SYM_LOOPS, 78)
+    with pytest.raises(B.BitgnnError) as e:
+        model.forward_fused(dev(x))
+    assert e.value.code == B.ERR_RANGE
+    p0, p1 = model.params
+    h1 = model.act[1]
+    bad = lambda **kw: B.gcn2_fused(**{**dict(
+        ctx=ctx, adj=adj, x=dev(x), K0=64, ldx=64, w1bits=p0["wb"], C1=300,
+        w1_stride=p0["wb"].stride(0), T_mm=p0["t_mm"], T_agg=p0["t_agg"], w2bits=p1["wb"], M=7,
+        w2_stride=p1["wb"].stride(0), alpha=p1["alpha"], tmp_bits=model.tmp_bits, h_bits=h1,
+        h_stride=h1.stride(0), logits=model.logits, ldo=7), **kw})
+    for kw, code in ((dict(ldx=63), B.ERR_INVALID_ARG), (dict(h_stride=4), B.ERR_INVALID_ARG),
+                     (dict(ldo=6), B.ERR_INVALID_ARG), (dict(alpha=None), B.ERR_INVALID_ARG),
+                     (dict(M=0), B.ERR_INVALID_ARG),
+                     (dict(logits=model.logits.data_ptr() + 2), B.ERR_ALIGNMENT)):
+        with pytest.raises(B.BitgnnError) as e:
+            bad(**kw)
+        assert e.value.code == code, kw
+    adj.close()
+
+
 @pytest.mark.parametrize("cfg", [2, 3])
 def test_model_full_size(B, ctx, cfg):
     _check_model(B, ctx, W.make_workload(cfg))
