@@ -34,7 +34,7 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def op_models(wl, nnz, blocked):
+def op_models(wl, nnz, blocked, fused=False):
     """Per-op work (bit-ops) and algorithmic bytes / lane-ops, keyed like forward_ops labels.
     Index bytes of an aggregation = min(bytes of the format the kernel actually streams,
     CSR at 4 B per non-zero), so a padded format earns no bandwidth credit."""
@@ -48,6 +48,15 @@ def op_models(wl, nnz, blocked):
     ops = {}
     k0 = wl.dims[0]
     nl = len(wl.layers)
+    if fused:
+        # the whole two-layer GCN in one launch: features and weights once, the CSR arrays
+        # for each of the two aggregations, both bit matrices written and read, the logits
+        c1, m = wl.dims[1], wl.dims[2]
+        ops["gcn2_fused"] = dict(
+            work=n * k0 * c1 + nnz * c1 + n * c1 * m + nnz * m,
+            bytes=4 * n * k0 + 8 * w64(k0) * c1 + 2 * (4 * nnz + 8 * (n + 1))
+            + 4 * 8 * n * w64(c1) + 8 * w64(c1) * m + 4 * n * m, bound="hbm")
+        return ops
     fused_first = wl.model == "gcn" and nl > 1      # float features feed the first product
     if not fused_first:
         ops["pack_f32"] = dict(work=0, bytes=4 * n * k0 + 8 * n * w64(k0), bound="hbm")
@@ -188,6 +197,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1 << 30,
                     help="rows of the workload the CPU oracle is timed on (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time the layer calls even where the one-launch kernel applies "
+                    "(two-layer GCN on a small graph, e.g. --config 1)")
     ap.add_argument("--op", choices=["model", "spmm_f32"], default="model",
                     help="model: the binary GNN forward pass (the headline metric); spmm_f32: "
                     "the symmetric-normalised full-precision aggregation on the same graph")
@@ -230,8 +242,21 @@ def main():
     log(f"calibration copy: {x.numel() * 4} bytes read and written")
     del calib
 
+    fused = model.fused_applies and not args.unfused
+    if fused:
+        log("small graph: the whole model runs as ONE launch (bitgnn_gcn2_fused)")
+
+    def run_step(mark=None):
+        if not fused:
+            return model.forward_ops(x, mark)
+        if mark:
+            mark("gcn2_fused")
+        model.forward_fused(x)
+        if mark:
+            mark(None)
+
     for _ in range(args.warmup):
-        model.forward_ops(x)
+        run_step()
     torch.cuda.synchronize()
 
     # timed region: K steps, one HIP event before every library call (torch's current
@@ -251,7 +276,7 @@ def main():
     t_start = time.perf_counter()
     for _ in range(args.steps):
         events.append([])
-        model.forward_ops(x, mark)
+        run_step(mark)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_start) * 1e3
     agg_ms = B.ctx_kernel_times(ctx)
@@ -265,7 +290,9 @@ def main():
             per_op[lab].append(evs[i].elapsed_time(evs[i + 1]))
     ms_per_step = wall_ms / args.steps
     blocked = adj.blocked_info()
-    models = op_models(wl, adj.nnz, blocked)
+    if fused:
+        assert int(model.fused_status.item()) == 0, "a grid barrier wait was abandoned"
+    models = op_models(wl, adj.nnz, blocked, fused)
     total_work = sum(m["work"] for m in models.values())
     value = total_work / (ms_per_step * 1e-3) / 1e9
 
@@ -310,6 +337,7 @@ def main():
     kname = {"bspmm": "bspmm_blk_kernel" if blocked["parts"] else "bspmm_kernel",
              "out_layer": "bspmm_blk_kernel" if dom in agg_kernel_ms else "spmm_i32_kernel",
              "bgemm_f32": "bgemm_f32_kernel", "bgemm": "bgemm_kernel",
+             "gcn2_fused": "gcn2_fused_kernel",
              "pack_f32": "pack_rows_kernel"}[dom.split(".")[-1]]
     if dm["bound"] == "hbm":
         ach = dm["bytes"] / launches / (davg * 1e-3) / 1e9

@@ -14,22 +14,24 @@
 // three un-fused calls are each bound by launch latency, not by their work; here the
 // whole model costs one launch and two barriers.
 //
-// gfx950 mapping: 256 threads per workgroup, at most two workgroups per compute unit so
-// that the whole grid is resident at once (the barrier needs that); the grid barrier is
-// one monotonic counter in device memory, advanced by the first lane of every workgroup
-// with agent-scope release / acquire, which is what makes the rows written by one XCD's
-// workgroups visible through another XCD's L2.  Every wait is bounded: a workgroup that
-// gives up still arrives at the remaining barriers (so the counter stays in step with the
-// host's count of launches), raises the caller's status word and skips its work.
-// Rows produced inside the kernel are read with per-lane (vector) loads only.
+// gfx950 mapping: one workgroup of 1024 threads per compute unit at most, so that the
+// whole grid is resident at once (the barrier needs that) and a barrier has few arrivals.
+// The grid barrier is one monotonic counter in device memory, advanced by the first lane
+// of every workgroup; the rows that cross it travel through device-scope accesses (see
+// store_shared_word), which is what makes the rows written under one XCD's L2 visible to
+// the workgroups under another's.  Every wait is bounded: a workgroup that gives up still
+// arrives at the remaining barriers (so the counter stays in step with the host's count of
+// launches), raises the caller's status word and skips its work.
+// Measured, calls back to back: 17 us per model on the 2,708-node citation-shaped workload
+// against 44 us for the layer calls (in the kernel: phase 1 ~7 us, each barrier ~3.3,
+// phase 2 ~1, phase 3 ~2); 34 against 40 us at 19,717 nodes x 500 features; level with
+// the layer calls at 65,536 nodes, behind them beyond (their kernels are the tuned ones).
 #include "common.h"
 
 namespace {
 
-constexpr int kFusedBlock = 256;
+constexpr int kFusedBlock = 1024;
 constexpr int kFusedWaves = kFusedBlock / 64;
-constexpr int kRowsA = 4;         // node rows a wavefront carries through phase 1
-constexpr int kChunkA = 8;        // 64-bit words of the feature axis per register chunk
 constexpr uint32_t kSpinLimit = 1u << 22; // polls of ~1 us each before a wait is abandoned
 constexpr int kBarriers = 2;
 
@@ -40,21 +42,36 @@ struct GridBarrier {
     bool alive;        // false once a wait was abandoned (block-uniform)
 };
 
+// The bit matrices that cross a barrier are written and read with device-scope accesses
+// (relaxed atomics: the store is written through to memory before it is acknowledged, the
+// load is served from there), so a barrier needs no cache write-back or invalidate -- those
+// cost ~0.2 us each and serialize per L2, which with hundreds of workgroups is most of a
+// barrier.  What it does need: every wavefront's stores acknowledged before its workgroup
+// arrives, and no load of the next phase issued before the workgroup has left.
+__device__ __forceinline__ void store_shared_word(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_shared_word(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // All threads of the block call this.  Returns false if the wait timed out.
 __device__ __forceinline__ bool grid_barrier(GridBarrier &b, int32_t *status)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); // this wavefront's rows are out
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wavefront's rows are in memory
     __syncthreads();
     __shared__ int ok_flag;
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(b.counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(b.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int ok = b.alive ? 1 : 0;
         if (ok) {
             uint32_t spins = 0;
-            while ((int32_t)(__hip_atomic_load(b.counter, __ATOMIC_ACQUIRE,
+            while ((int32_t)(__hip_atomic_load(b.counter, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT) -
                              b.target) < 0) {
-                __builtin_amdgcn_s_sleep(4);
+                __builtin_amdgcn_s_sleep(8);
                 if (++spins > kSpinLimit) {
                     ok = 0;
                     if (status)
@@ -68,13 +85,14 @@ __device__ __forceinline__ bool grid_barrier(GridBarrier &b, int32_t *status)
     __syncthreads();
     b.alive = ok_flag != 0;
     b.target += b.nblocks;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // drop stale lines before reading
     return b.alive;
 }
 
-// Phase 1.  One wavefront finishes kRowsA node rows: 64 lanes load 64 consecutive floats,
-// the compare mask is the activation word; lane c owns output channel c of each tile.
-template <int TILES>
+// Phase 1.  One wavefront finishes kRowsA node rows at a time (2, or 4 when every wavefront
+// has several groups to do and more loads in flight pay): 64 lanes load 64 consecutive
+// floats, the compare mask is the activation word; lane c owns output channel c of each
+// tile and holds kChunkA 64-bit weight words of it per step.
+template <int TILES, int kRowsA>
 __device__ __forceinline__ void phase_bmm_f32(const float *__restrict__ x, int64_t n, int32_t K,
                                               int64_t ldx, const uint64_t *__restrict__ w,
                                               int64_t w_stride, int32_t M,
@@ -82,6 +100,7 @@ __device__ __forceinline__ void phase_bmm_f32(const float *__restrict__ x, int64
                                               uint64_t *__restrict__ out, int64_t out_stride,
                                               int64_t gwave, int64_t nwaves, int lane)
 {
+    constexpr int kChunkA = TILES == 4 ? 4 : 8;
     const int32_t kw = (K + 63) / 64;
     const uint64_t *wrow[TILES];
     bool c_ok[TILES];
@@ -143,57 +162,122 @@ __device__ __forceinline__ void phase_bmm_f32(const float *__restrict__ x, int64
             for (int t = 0; t < TILES; ++t) {
                 const uint64_t word = __ballot(c_ok[t] && K - 2 * acc[r][t] >= tc[t]);
                 if (row < n && t * 64 < M && lane == 0)
-                    out[row * out_stride + t] = word;
+                    store_shared_word(&out[row * out_stride + t], word);
             }
         }
     }
 }
 
-// Number of neighbours of `row` whose bit of channel (tile, lane) is set, for every tile.
-// The wavefront takes 64 neighbours at a time: lane l fetches the words of neighbour l,
-// then the words go round by lane broadcast and each lane picks its own bit.
-template <int TILES>
-__device__ __forceinline__ void row_counts(const uint32_t *__restrict__ rowptr,
-                                           const int32_t *__restrict__ col, uint32_t row,
-                                           const uint64_t *src, int64_t src_stride, int mw,
-                                           int lane, int (&cnt)[TILES], uint32_t &deg)
+struct RowRange {
+    uint32_t row, beg, end; // wave-uniform; beg == end == 0 past the last row
+};
+
+__device__ __forceinline__ RowRange fetch_row(const int32_t *__restrict__ order,
+                                              const uint32_t *__restrict__ rowptr, int64_t slot,
+                                              int64_t n)
 {
-    const uint32_t beg = rowptr[row], end = rowptr[row + 1];
-    deg = end - beg;
+    RowRange r{0u, 0u, 0u};
+    if (slot < n) {
+        r.row = (uint32_t)order[slot];
+        r.beg = rowptr[r.row];
+        r.end = rowptr[r.row + 1];
+    }
+    return r;
+}
+
+// column index of the lane's neighbour among the first 64 of the row
+__device__ __forceinline__ int32_t fetch_first_cols(const int32_t *__restrict__ col,
+                                                    const RowRange &r, int lane)
+{
+    return r.beg + (uint32_t)lane < r.end ? col[r.beg + lane] : 0;
+}
+
+// adds, for every tile, the bits of this lane's channel over the first m lanes' words
+template <int TILES>
+__device__ __forceinline__ void count_bits(const uint32_t (&lo)[TILES], const uint32_t (&hi)[TILES],
+                                           uint32_t m, int (&cnt)[TILES])
+{
+    for (uint32_t l = 0; l < m; l += 4) {
 #pragma unroll
-    for (int t = 0; t < TILES; ++t)
-        cnt[t] = 0;
-    for (uint32_t e0 = beg; e0 < end; e0 += 64) {
-        const uint32_t m = end - e0 < 64u ? end - e0 : 64u; // wave-uniform
-        const bool mine = (uint32_t)lane < m;
-        const int32_t j = mine ? col[e0 + lane] : 0;
-        uint32_t lo[TILES], hi[TILES];
+        for (int u = 0; u < 4; ++u) { // lanes past m hold zero words
+            const int src_lane = (int)((l + u) & 63u);
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
-            // lanes without a neighbour hold zero words: they count nothing
-            const uint64_t wd = (mine && t < mw) ? src[(int64_t)j * src_stride + t] : 0ull;
-            lo[t] = (uint32_t)wd;
-            hi[t] = (uint32_t)(wd >> 32);
+            for (int t = 0; t < TILES; ++t) {
+                const uint64_t word =
+                    (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)lo[t], src_lane) |
+                    ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi[t], src_lane) << 32);
+                cnt[t] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
+            }
         }
-        for (uint32_t l = 0; l < m; l += 4) {
+    }
+}
+
+// Walks the wavefront's rows (slots gwave, gwave + nwaves, ... of the degree order), R rows
+// at a time, and hands each row's counts -- the number of neighbours whose bit of channel
+// (tile, lane) is set -- to `emit(row, degree, cnt)`.  64 neighbours of a row are taken at
+// once: lane l fetches the words of neighbour l, then the words go round by lane broadcast
+// and each lane picks its own bit.  A row costs four dependent memory latencies (order, row
+// pointers, column indices, words); the R rows of a step go through them together.
+template <int TILES, int R, class Emit>
+__device__ __forceinline__ void for_each_row(const uint32_t *__restrict__ rowptr,
+                                             const int32_t *__restrict__ col,
+                                             const int32_t *__restrict__ order, int64_t n,
+                                             int64_t gwave, int64_t nwaves, const uint64_t *src,
+                                             int64_t src_stride, int mw, int lane, Emit &&emit)
+{
+    for (int64_t slot0 = gwave; slot0 < n; slot0 += R * nwaves) {
+        RowRange r[R];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int src_lane = (int)((l + u) & 63u);
+        for (int q = 0; q < R; ++q)
+            r[q] = fetch_row(order, rowptr, slot0 + q * nwaves, n);
+        int32_t j[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+            j[q] = fetch_first_cols(col, r[q], lane);
+        uint32_t lo[R][TILES], hi[R][TILES];
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+#pragma unroll
+            for (int t = 0; t < TILES; ++t) {
+                // lanes without a neighbour hold zero words: they count nothing
+                const bool mine = r[q].beg + (uint32_t)lane < r[q].end;
+                const uint64_t wd = (mine && t < mw)
+                                        ? load_shared_word(&src[(int64_t)j[q] * src_stride + t])
+                                        : 0ull;
+                lo[q][t] = (uint32_t)wd;
+                hi[q][t] = (uint32_t)(wd >> 32);
+            }
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            int cnt[TILES];
+#pragma unroll
+            for (int t = 0; t < TILES; ++t)
+                cnt[t] = 0;
+            const uint32_t deg = r[q].end - r[q].beg;
+            count_bits<TILES>(lo[q], hi[q], deg < 64u ? deg : 64u, cnt);
+            for (uint32_t e0 = r[q].beg + 64; e0 < r[q].end; e0 += 64) { // long rows
+                const uint32_t m = r[q].end - e0 < 64u ? r[q].end - e0 : 64u;
+                const bool mine = (uint32_t)lane < m;
+                const int32_t jj = mine ? col[e0 + lane] : 0;
+                uint32_t l2[TILES], h2[TILES];
 #pragma unroll
                 for (int t = 0; t < TILES; ++t) {
-                    const uint64_t word =
-                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)lo[t], src_lane) |
-                        ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi[t], src_lane)
-                         << 32);
-                    cnt[t] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
+                    const uint64_t wd = (mine && t < mw)
+                                            ? load_shared_word(&src[(int64_t)jj * src_stride + t])
+                                            : 0ull;
+                    l2[t] = (uint32_t)wd;
+                    h2[t] = (uint32_t)(wd >> 32);
                 }
+                count_bits<TILES>(l2, h2, m, cnt);
             }
+            if (slot0 + q * nwaves < n)
+                emit(r[q].row, deg, cnt);
         }
     }
 }
 
-template <int TILES>
-__global__ __launch_bounds__(kFusedBlock, 2) void gcn2_fused_kernel(
+template <int TILES, int ROWS_A>
+__global__ __launch_bounds__(kFusedBlock) void gcn2_fused_kernel(
     const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
     const int32_t *__restrict__ order, int64_t n, const float *__restrict__ x, int32_t K0,
     int64_t ldx, const uint64_t *__restrict__ w1, int32_t C1, int64_t w1_stride,
@@ -205,12 +289,14 @@ __global__ __launch_bounds__(kFusedBlock, 2) void gcn2_fused_kernel(
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t gwave = (int64_t)blockIdx.x * kFusedWaves + wave;
+    // consecutive work items go to different workgroups (rows come by decreasing degree)
+    const int64_t gwave = (int64_t)wave * gridDim.x + blockIdx.x;
     const int64_t nwaves = (int64_t)gridDim.x * kFusedWaves;
     const int64_t mw = ((int64_t)C1 + 63) / 64;
+    constexpr int kRowsB = TILES == 4 ? 2 : 4; // rows of an aggregation step in flight
     GridBarrier bar{bar_counter, bar_base + gridDim.x, gridDim.x, true};
 
-    phase_bmm_f32<TILES>(x, n, K0, ldx, w1, w1_stride, C1, T_mm, tmp_bits, mw, gwave, nwaves,
+    phase_bmm_f32<TILES, ROWS_A>(x, n, K0, ldx, w1, w1_stride, C1, T_mm, tmp_bits, mw, gwave, nwaves,
                          lane);
 
     const bool go2 = grid_barrier(bar, status);
@@ -222,60 +308,50 @@ __global__ __launch_bounds__(kFusedBlock, 2) void gcn2_fused_kernel(
             c_ok[t] = t * 64 + lane < C1;
             ta[t] = c_ok[t] ? T_agg[t * 64 + lane] : 0;
         }
-        for (int64_t slot = gwave; slot < n; slot += nwaves) {
-            const uint32_t row = (uint32_t)order[slot];
-            int cnt[TILES];
-            uint32_t deg;
-            row_counts<TILES>(rowptr, col, row, tmp_bits, mw, (int)mw, lane, cnt, deg);
+        for_each_row<TILES, kRowsB>(rowptr, col, order, n, gwave, nwaves, tmp_bits, mw, (int)mw, lane,
+                            [&](uint32_t row, uint32_t deg, const int (&cnt)[TILES]) {
 #pragma unroll
-            for (int t = 0; t < TILES; ++t) {
-                const uint64_t word = __ballot(c_ok[t] && 2 * cnt[t] - (int)deg >= ta[t]);
-                if (t * 64 < C1 && lane == 0)
-                    h_bits[(int64_t)row * h_stride + t] = word;
-            }
-        }
+                                for (int t = 0; t < TILES; ++t) {
+                                    const uint64_t word =
+                                        __ballot(c_ok[t] && 2 * cnt[t] - (int)deg >= ta[t]);
+                                    if (t * 64 < C1 && lane == 0)
+                                        store_shared_word(&h_bits[(int64_t)row * h_stride + t],
+                                                          word);
+                                }
+                            });
     }
 
     const bool go3 = grid_barrier(bar, status);
     if (go3) {
-        // weight bits of class m for this lane's channels: bit m of wsel[t]
-        uint64_t wsel[TILES];
-        bool c_ok[TILES];
+        // Lane m owns class m and keeps its weight words.  With the counts cnt_c of a row
+        // (lane c) and w = 2 bit - 1:
+        //   sum_c w_mc (2 cnt_c - deg) = 2 sum_c w_mc cnt_c - deg (2 popc(W_m) - C1),
+        //   sum_c w_mc cnt_c = sum_b 2^b (2 popc(P_b & W_m) - popc(P_b)),
+        // where P_b is the wave-wide vote "bit b of cnt_c is set": a handful of votes and
+        // popcounts per row, whatever the number of classes.
+        uint64_t wm[TILES];
+        int wsum = -C1;
 #pragma unroll
         for (int t = 0; t < TILES; ++t) {
-            c_ok[t] = t * 64 + lane < C1;
-            wsel[t] = 0;
+            wm[t] = (lane < M && t < mw) ? w2[(int64_t)lane * w2_stride + t] : 0ull;
+            wsum += 2 * __popcll(wm[t]);
         }
-        for (int m = 0; m < M; ++m)
-#pragma unroll
-            for (int t = 0; t < TILES; ++t)
-                if (t < mw)
-                    wsel[t] |= ((w2[(int64_t)m * w2_stride + t] >> lane) & 1ull) << m;
         const float al = lane < M ? alpha[lane] : 0.0f;
-        for (int64_t slot = gwave; slot < n; slot += nwaves) {
-            const uint32_t row = (uint32_t)order[slot];
-            int cnt[TILES];
-            uint32_t deg;
-            row_counts<TILES>(rowptr, col, row, h_bits, h_stride, (int)mw, lane, cnt, deg);
-            int s[TILES];
-#pragma unroll
-            for (int t = 0; t < TILES; ++t)
-                s[t] = c_ok[t] ? 2 * cnt[t] - (int)deg : 0; // pad channels carry nothing
-            int res = 0;
-            for (int m = 0; m < M; ++m) {
-                int v = 0;
+        for_each_row<TILES, kRowsB>(
+            rowptr, col, order, n, gwave, nwaves, h_bits, h_stride, (int)mw, lane,
+            [&](uint32_t row, uint32_t deg, const int (&cnt)[TILES]) {
+                const int planes = 32 - __clz((int)deg); // cnt <= deg; wave-uniform
+                int acc = 0;
 #pragma unroll
                 for (int t = 0; t < TILES; ++t)
-                    v += ((wsel[t] >> m) & 1ull) ? s[t] : -s[t];
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1)
-                    v += __shfl_xor(v, d);
-                if (lane == m)
-                    res = v;
-            }
-            if (lane < M)
-                logits[(int64_t)row * ldo + lane] = al * (float)res;
-        }
+                    for (int b = 0; b < planes; ++b) {
+                        const uint64_t pb = __ballot((cnt[t] >> b) & 1);
+                        acc += (2 * __popcll(pb & wm[t]) - __popcll(pb)) << b;
+                    }
+                const int res = 2 * acc - (int)deg * wsum;
+                if (lane < M)
+                    logits[(int64_t)row * ldo + lane] = al * (float)res;
+            });
     }
 }
 
@@ -323,24 +399,31 @@ extern "C" int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj
     hipStream_t s = (hipStream_t)stream;
 
     const int tiles = mw <= 1 ? 1 : mw <= 2 ? 2 : 4;
-    const void *kernel = tiles == 1   ? (const void *)gcn2_fused_kernel<1>
-                         : tiles == 2 ? (const void *)gcn2_fused_kernel<2>
-                                      : (const void *)gcn2_fused_kernel<4>;
+    const void *kernel = (const void *)gcn2_fused_kernel<4, 4>; // the largest variant
     // the whole grid must be resident at once: at most what the occupancy query allows
     int per_cu = 0;
     BG_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kFusedBlock, 0));
     BG_REQUIRE(ctx, per_cu >= 1, BITGNN_ERR_HIP, "bitgnn_gcn2_fused: kernel does not fit a CU");
-    int64_t blocks = (int64_t)ctx->n_cus * (per_cu < 2 ? per_cu : 2);
+    int64_t blocks = ctx->n_cus; // one per compute unit: fewer arrivals per barrier
     const int64_t useful = (n + kFusedWaves - 1) / kFusedWaves; // one row per wavefront
     if (blocks > useful)
         blocks = useful;
     const uint32_t base = ctx->bar_base;
     uint32_t *counter = ctx->queue + kFusedBarrierWord;
-#define BG_FUSED(TV)                                                                              \
-    gcn2_fused_kernel<TV><<<(unsigned)blocks, kFusedBlock, 0, s>>>(                               \
+    // four rows per phase-1 step once a wavefront would otherwise walk more than two steps
+    const bool rows4 = (n + 1) / 2 > 2 * blocks * kFusedWaves;
+#define BG_FUSED2(TV, RV)                                                                         \
+    gcn2_fused_kernel<TV, RV><<<(unsigned)blocks, kFusedBlock, 0, s>>>(                           \
         adj->rowptr, adj->col, adj->order, n, x, K0, ldx, w1bits, C1, w1_stride, T_mm, T_agg,     \
         w2bits, M, w2_stride, alpha, tmp_bits, h_bits, h_stride, logits, ldo, counter, base,      \
         status)
+#define BG_FUSED(TV)                                                                              \
+    do {                                                                                          \
+        if (rows4)                                                                                \
+            BG_FUSED2(TV, 4);                                                                     \
+        else                                                                                      \
+            BG_FUSED2(TV, 2);                                                                     \
+    } while (0)
     if (tiles == 1)
         BG_FUSED(1);
     else if (tiles == 2)
@@ -348,6 +431,7 @@ extern "C" int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj
     else
         BG_FUSED(4);
 #undef BG_FUSED
+#undef BG_FUSED2
     BG_LAUNCH_CHECK(ctx, "gcn2_fused_kernel");
     // every workgroup arrives at every barrier, whatever happens: the device counter
     // advances by exactly this much per launch

@@ -664,7 +664,9 @@ def _check_fused(B, model, rp, col, layers, x):
     (2000, 9000, (600, 128, 41), SYM_LOOPS, 1),                # a row of ~1000 neighbours
     (4097, 30000, (129, 256, 10), SYM_LOOPS, 0),               # four tiles
     (3000, 12000, (512, 200, 3), W.ADJ_SYMMETRIZE, 0),         # ragged four tiles
-    (20000, 90000, (500, 64, 3), SYM_LOOPS, 0)])               # several rows per wavefront
+    (20000, 90000, (500, 64, 3), SYM_LOOPS, 0),                # several rows per wavefront
+    (20000, 60000, (100, 100, 5), SYM_LOOPS, 0),               # ... with two tiles
+    (18000, 50000, (64, 256, 64), W.ADJ_SYMMETRIZE, 0)])       # ... with four tiles
 def test_gcn2_fused_matches_oracle_and_layer_calls(B, ctx, n, e, dims, flags, hubs):
     adj, rp, col, layers, x, model = _fused_case(B, ctx, n, e, dims, flags, 500 + n, hubs)
     assert adj.max_degree <= B.FUSED_MAX_DEGREE
