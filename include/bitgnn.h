@@ -322,6 +322,12 @@ int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_ad
  * One fused call at a time per context (the barrier counter lives in the context); it is
  * asynchronous on `stream` like every other call.  All pointers are device pointers owned
  * by the caller. */
+/* Bound on the polls (~1 us each) of one wait at a barrier of bitgnn_gcn2_fused before
+ * the wait is abandoned; default 2^22.  polls >= 1.  A tiny bound makes workgroups that
+ * arrive early give up: the way to exercise the abandoned-wait path (status raised, every
+ * workgroup still exits, the next call works) without taking compute units away. */
+int bitgnn_ctx_set_fused_spin_limit(bitgnn_ctx *ctx, uint32_t polls);
+
 int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const float *x,
                       int32_t K0, int64_t ldx, const uint64_t *w1bits, int32_t C1,
                       int64_t w1_stride, const int32_t *T_mm, const int32_t *T_agg,

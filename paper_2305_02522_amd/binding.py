@@ -81,6 +81,7 @@ _SIGNATURES = {
                                              _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_sage_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp,
                                           _vp, _vp, _vp, _i64]),
+    "bitgnn_ctx_set_fused_spin_limit": (_int, [_vp, _u32]),
     "bitgnn_gcn2_fused": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _i32, _i64, _vp, _vp, _vp,
                                  _i32, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
 }
@@ -319,6 +320,10 @@ def sage_out_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg,
 
 
 FUSED_MAX_NODES, FUSED_MAX_DEGREE, FUSED_MAX_HIDDEN, FUSED_MAX_CLASSES = 65536, 1024, 256, 64
+
+
+def ctx_set_fused_spin_limit(ctx: Context, polls: int):
+    ctx.check(_lib.bitgnn_ctx_set_fused_spin_limit(ctx.handle, polls))
 
 
 def gcn2_fused(ctx: Context, adj, x, K0, ldx, w1bits, C1, w1_stride, T_mm, T_agg, w2bits, M,

@@ -17,6 +17,7 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
     ctx->cb_nodes = 8192;
     ctx->part_len = 255;
     ctx->min_avg_degree = 8;
+    ctx->fused_spin_limit = 1u << 22;
     if (const char *e = getenv("BITGNN_BGEMM"))
         ctx->bgemm_path = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma") ? 2 : 0;
     if (device >= 0) {

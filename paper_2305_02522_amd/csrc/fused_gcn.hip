@@ -32,13 +32,13 @@ namespace {
 
 constexpr int kFusedBlock = 1024;
 constexpr int kFusedWaves = kFusedBlock / 64;
-constexpr uint32_t kSpinLimit = 1u << 22; // polls of ~1 us each before a wait is abandoned
 constexpr int kBarriers = 2;
 
 struct GridBarrier {
     uint32_t *counter; // device word, only ever incremented
     uint32_t target;   // value that means "everyone arrived at the next barrier"
     uint32_t nblocks;
+    uint32_t spin_limit; // polls of ~1 us each before a wait is abandoned
     bool alive;        // false once a wait was abandoned (block-uniform)
 };
 
@@ -72,7 +72,7 @@ __device__ __forceinline__ bool grid_barrier(GridBarrier &b, int32_t *status)
                                                __HIP_MEMORY_SCOPE_AGENT) -
                              b.target) < 0) {
                 __builtin_amdgcn_s_sleep(8);
-                if (++spins > kSpinLimit) {
+                if (++spins > b.spin_limit) {
                     ok = 0;
                     if (status)
                         atomicAdd(status, 1);
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kFusedBlock) void gcn2_fused_kernel(
     const uint64_t *__restrict__ w2, int32_t M, int64_t w2_stride,
     const float *__restrict__ alpha, uint64_t *tmp_bits, uint64_t *h_bits, int64_t h_stride,
     float *__restrict__ logits, int64_t ldo, uint32_t *bar_counter, uint32_t bar_base,
-    int32_t *status)
+    uint32_t spin_limit, int32_t *status)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kFusedBlock) void gcn2_fused_kernel(
     const int64_t nwaves = (int64_t)gridDim.x * kFusedWaves;
     const int64_t mw = ((int64_t)C1 + 63) / 64;
     constexpr int kRowsB = TILES == 4 ? 2 : 4; // rows of an aggregation step in flight
-    GridBarrier bar{bar_counter, bar_base + gridDim.x, gridDim.x, true};
+    GridBarrier bar{bar_counter, bar_base + gridDim.x, gridDim.x, spin_limit, true};
 
     phase_bmm_f32<TILES, ROWS_A>(x, n, K0, ldx, w1, w1_stride, C1, T_mm, tmp_bits, mw, gwave, nwaves,
                          lane);
@@ -357,6 +357,16 @@ __global__ __launch_bounds__(kFusedBlock) void gcn2_fused_kernel(
 
 } // namespace
 
+extern "C" int bitgnn_ctx_set_fused_spin_limit(bitgnn_ctx *ctx, uint32_t polls)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, polls >= 1, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_ctx_set_fused_spin_limit: polls must be >= 1");
+    ctx->fused_spin_limit = polls;
+    return BITGNN_OK;
+}
+
 extern "C" int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                                  const float *x, int32_t K0, int64_t ldx, const uint64_t *w1bits,
                                  int32_t C1, int64_t w1_stride, const int32_t *T_mm,
@@ -416,7 +426,7 @@ extern "C" int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj
     gcn2_fused_kernel<TV, RV><<<(unsigned)blocks, kFusedBlock, 0, s>>>(                           \
         adj->rowptr, adj->col, adj->order, n, x, K0, ldx, w1bits, C1, w1_stride, T_mm, T_agg,     \
         w2bits, M, w2_stride, alpha, tmp_bits, h_bits, h_stride, logits, ldo, counter, base,      \
-        status)
+        ctx->fused_spin_limit, status)
 #define BG_FUSED(TV)                                                                              \
     do {                                                                                          \
         if (rows4)                                                                                \

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "bitgnn.h")).read()
     declared = set(re.findall(r"\b(bitgnn_[a-z0-9_]+)\s*\(", header))
-    assert len(declared) >= 24
+    assert len(declared) >= 25
     assert declared == set(B.EXPORTS)
     import ctypes
     lib = ctypes.CDLL(B.LIB_PATH)
@@ -100,6 +100,12 @@ def test_aggregation_and_layer_validation(vctx):
         B.ERR_INVALID_ARG
     assert _code(B.gcn2_fused, vctx, None, P8, 100, 100, P8, 64, 2, P8, P8, P8, 7, 1, P8, P8, P8,
                  1, P8, 7) == B.ERR_INVALID_ARG
+
+
+def test_fused_spin_limit_validation(vctx):
+    B.ctx_set_fused_spin_limit(vctx, 1)
+    B.ctx_set_fused_spin_limit(vctx, 1 << 22)
+    assert _code(B.ctx_set_fused_spin_limit, vctx, 0) == B.ERR_INVALID_ARG
 
 
 def test_ctx_create_rejects_bad_device():

@@ -697,6 +697,33 @@ def test_gcn2_fused_config1_full_size(B, ctx):
     adj.close()
 
 
+def test_gcn2_fused_abandoned_wait_is_reported_and_recovered_from(B, ctx):
+    """Failure path of the grid barrier, forced from the host: with a bound of one poll the
+    workgroups that arrive early give up.  Every workgroup must still exit, the status word
+    must say so, and the next call (default bound) must be right: the arrival counter stays
+    in step because a workgroup that gave up still arrives at the later barriers."""
+    adj, rp, col, layers, x, model = _fused_case(B, ctx, 20000, 90000, (500, 64, 3), SYM_LOOPS,
+                                                 4242)
+    want_logits, want_h = _check_fused(B, model, rp, col, layers, x)
+    B.ctx_set_fused_spin_limit(ctx, 1)
+    try:
+        model.forward_fused(dev(x))
+        torch.cuda.synchronize()
+    finally:
+        B.ctx_set_fused_spin_limit(ctx, 1 << 22)
+    gave_up = int(model.fused_status.item())
+    assert gave_up >= 1, "no wait was abandoned with a bound of one poll"
+    model.act[1].zero_()
+    model.logits.zero_()
+    again = model.forward_fused(dev(x))
+    torch.cuda.synchronize()
+    assert int(model.fused_status.item()) == gave_up          # sticky, nothing new
+    assert torch.equal(again, want_logits) and torch.equal(model.act[1], want_h)
+    with pytest.raises(B.BitgnnError):
+        B.ctx_set_fused_spin_limit(ctx, 0)
+    adj.close()
+
+
 def test_gcn2_fused_rejects_what_it_cannot_run(B, ctx):
     """Outside its range the call fails before launching, naming the limits."""
     adj, rp, col, layers, x, model = _fused_case(B, ctx, 3000, 9000, (64, 64, 7), SYM_LOOPS, 77,
