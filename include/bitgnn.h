@@ -226,6 +226,20 @@ int bitgnn_spmm_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const 
                     int x_is_bits, int32_t C, int64_t ldx, const float *r, const float *f,
                     int epilogue, const float *tau, void *out, int64_t ldo);
 
+/* ADD, the auxiliary merge of two activation tensors (Section 3.1.2: ADD.BBF and ADD.FFF
+ * merge the self-connectivity of GraphSAGE), with BIN optionally folded in:
+ *   y[i][c] = a[i][c] + b[i][c],  c < C,  one rounded float addition.
+ * a, b: x_is_bits == 0: float [n][ld];  != 0: packed +-1 rows, uint64 [n][ld] (read as
+ *       +1.0 / -1.0; ADD.BBF is both operands in bits).
+ * epilogue SCALE_F32:   out = float [n][ldo] <- y
+ *          THRESH_BITS: out = uint64 [n][ldo], ceil(C/64) words per row, bit c = (y >= tau[c]),
+ *                       pad bits zero; needs tau (float [C]).
+ * out must not overlap a or b.  n == 0 is a no-op.
+ * All pointers are device pointers owned by the caller; asynchronous on `stream`. */
+int bitgnn_add(bitgnn_ctx *ctx, void *stream, const void *a, int a_is_bits, int64_t lda,
+               const void *b, int b_is_bits, int64_t ldb, int64_t n, int32_t C, int epilogue,
+               const float *tau, void *out, int64_t ldo);
+
 /* ---- layers (Section 3.1.2 high-level functions; Table 3 caption recipe) - */
 
 /* GCN hidden layer, BMM.xBB + BSpMM.BBB:

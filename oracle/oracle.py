@@ -210,6 +210,24 @@ def rebin_f32(y: np.ndarray, tau: np.ndarray) -> np.ndarray:
     return v
 
 
+def add_f32(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """ADD, the auxiliary merge of two activation tensors (Section 3.1.2, ADD.BBF /
+    ADD.FFF): element-wise a + b in float32 (the paper's full precision), one rounded
+    addition.  Operands are float32 arrays or +-1 int8 arrays (binary tensors)."""
+    assert a.shape == b.shape and a.ndim == 2
+    fa = np.ascontiguousarray(a, dtype=np.float32)
+    fb = np.ascontiguousarray(b, dtype=np.float32)
+    return np.add(fa, fb, dtype=np.float32)
+
+
+def sage_hidden_layer_added(rowptr, col, v, w_self, w_nb, t_agg, t_mm) -> np.ndarray:
+    """GraphSAGE hidden layer with the self-connectivity merged by addition (Section 2.1:
+    X_i W1 + aggregate(X_j) W2; Section 3.1.2: the merge is an ADD of the two products),
+    in exact integers: bin(bmm(v, W1) + bmm(bin(A v), W2))."""
+    nb = _spmm_rebin(rowptr, col, v, t_agg)
+    return rebin(bmm(v, w_self) + bmm(nb, w_nb), t_mm)
+
+
 def scale(y: np.ndarray, alpha: np.ndarray) -> np.ndarray:
     y = _c(y, np.int64)
     alpha = _c(alpha, np.float32)

@@ -454,6 +454,90 @@ def test_spmm_f32_rejects_bad_arguments(B, ctx):
     adj.close()
 
 
+# ------------------------------------------------------------------ ADD (auxiliary merge)
+@pytest.mark.parametrize("n,C", [(1, 1), (77, 64), (300, 65), (5000, 200), (20000, 128)])
+@pytest.mark.parametrize("a_bits,b_bits", [(False, False), (True, True), (True, False),
+                                           (False, True)])
+def test_add_variants(B, ctx, n, C, a_bits, b_bits):
+    """ADD.FFF, ADD.BBF and the mixed forms, float result bit for bit and binarized again."""
+    r = np.random.default_rng(n * 7 + C)
+    wds = (C + 63) // 64
+
+    def operand(bits):
+        if bits:
+            v = W.pm1(r, (n, C))
+            return v, dev(orc.to_words(v).view(np.int64)), wds
+        f = r.standard_normal((n, C + 3)).astype(np.float32)[:, :C]      # padded leading dim
+        f[r.random((n, C)) < 0.1] = 0.0
+        d = dev(np.ascontiguousarray(np.pad(f, ((0, 0), (0, 3)))))
+        return f, d, C + 3
+
+    a, ad, lda = operand(a_bits)
+    b, bd, ldb = operand(b_bits)
+    want = orc.add_f32(a, b)
+    out = torch.full((n, C + 1), 7.0, dtype=torch.float32, device="cuda")
+    B.add(ctx, ad, a_bits, lda, bd, b_bits, ldb, n, C, B.EPI_SCALE_F32, None, out, C + 1)
+    tau = r.standard_normal(C).astype(np.float32)
+    tau[::3] = 0.0
+    ob = torch.full((n, wds + 1), -1, dtype=torch.int64, device="cuda")
+    B.add(ctx, ad, a_bits, lda, bd, b_bits, ldb, n, C, B.EPI_THRESH_BITS, dev(tau), ob, wds + 1)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:, :C].view(np.uint32), want.view(np.uint32))
+    assert np.all(got[:, C] == 7.0)                                       # padding untouched
+    gb = words_np(ob)
+    assert np.array_equal(gb[:, :wds], orc.to_words(orc.rebin_f32(want, tau)))
+    assert np.all(gb[:, wds] == np.uint64(0xFFFFFFFFFFFFFFFF))
+
+
+def test_add_merges_a_sage_layer_like_the_concatenated_form(B, ctx):
+    """ADD.FFF on the two scaled products of a GraphSAGE layer, binarized: the bits of the
+    library's concatenated layer."""
+    n, e, k, m = 3000, 30000, 100, 70
+    adj, rp, col, r = _graph(B, ctx, n, e, W.ADJ_SYMMETRIZE, 31)
+    v = W.pm1(r, (n, k))
+    w = W.pm1(r, (2 * k, m))
+    t_agg = r.integers(-3, 4, size=k).astype(np.int32)
+    t_mm = r.integers(-9, 10, size=m).astype(np.int32)
+    want = orc.sage_hidden_layer_added(rp, col, v, w[:k], w[k:], t_agg, t_mm)
+    kw, mw = (k + 63) // 64, (m + 63) // 64
+    vb = dev(orc.to_words(v).view(np.int64))
+    nb = torch.zeros((n, kw), dtype=torch.int64, device="cuda")
+    B.bspmm(ctx, adj, vb, k, kw, B.EPI_THRESH_BITS, dev(t_agg), nb, kw)
+    one = dev(np.ones(m, dtype=np.float32))
+    z = []
+    for xb, wpart in ((vb, w[:k]), (nb, w[k:])):
+        wb = torch.zeros((m, kw), dtype=torch.int64, device="cuda")
+        B.pack_weights_i8(ctx, dev(wpart), k, m, m, wb, kw)
+        zf = torch.empty((n, m), dtype=torch.float32, device="cuda")
+        B.bgemm(ctx, xb, n, kw, k, kw, wb, m, kw, B.EPI_SCALE_F32, None, one, zf, m)   # BMM.BBF
+        z.append(zf)
+    ob = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    B.add(ctx, z[0], False, m, z[1], False, m, n, m, B.EPI_THRESH_BITS,
+          dev(t_mm.astype(np.float32)), ob, mw)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(ob), orc.to_words(want))
+    adj.close()
+
+
+def test_add_rejects_bad_arguments(B, ctx):
+    f = torch.zeros((4, 70), dtype=torch.float32, device="cuda")
+    w = torch.zeros((4, 2), dtype=torch.int64, device="cuda")
+    for args, code in (
+            ((f, False, 69, f, False, 70, 4, 70, B.EPI_SCALE_F32, None, f, 70), B.ERR_INVALID_ARG),
+            ((f, False, 70, w, True, 1, 4, 70, B.EPI_SCALE_F32, None, f, 70), B.ERR_INVALID_ARG),
+            ((f, False, 70, f, False, 70, 4, 70, B.EPI_THRESH_BITS, None, w, 2), B.ERR_INVALID_ARG),
+            ((f, False, 70, f, False, 70, 4, 70, B.EPI_RAW_I32, None, f, 70), B.ERR_INVALID_ARG),
+            ((f, False, 70, f, False, 70, 4, 0, B.EPI_SCALE_F32, None, f, 70), B.ERR_INVALID_ARG),
+            ((f, False, 70, None, False, 70, 4, 70, B.EPI_SCALE_F32, None, f, 70), B.ERR_INVALID_ARG),
+            ((f, False, 70, w.data_ptr() + 4, True, 2, 4, 70, B.EPI_SCALE_F32, None, f, 70),
+             B.ERR_ALIGNMENT)):
+        with pytest.raises(B.BitgnnError) as e:
+            B.add(ctx, *args)
+        assert e.value.code == code, args
+    B.add(ctx, None, False, 70, None, False, 70, 0, 70, B.EPI_SCALE_F32, None, None, 70)  # n = 0
+
+
 # ------------------------------------------------------------------ whole models
 def _run_model(B, ctx, wl):
     adj = B.adj_build(ctx, dev(wl.src), dev(wl.dst), len(wl.src), wl.n, wl.adj_flags)

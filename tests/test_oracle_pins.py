@@ -483,3 +483,58 @@ def test_weighted_out_layer_reduces_to_the_integer_out_layer():
     assert np.array_equal(got, orc.gcn_out_layer(rp, col, v, w, one))
     y64 = orc.spmm_weighted(rp, col, orc.bmm(v, w).astype(np.float64))
     assert np.array_equal(got.astype(np.float64), y64)
+
+
+# ---------------------------------------------------------------------------
+# ADD: the auxiliary merge (Section 3.1.2)
+# ---------------------------------------------------------------------------
+
+def test_add_handworked_values_and_float32_rounding():
+    """ADD.BBF on +-1 tensors can only give -2, 0, 2; ADD.FFF is ONE float32 addition:
+    hand-worked cases where float32 and wider arithmetic differ, written as literals."""
+    a = np.array([[1, 1, -1, -1]], dtype=np.int8)
+    b = np.array([[1, -1, 1, -1]], dtype=np.int8)
+    assert orc.add_f32(a, b).tolist() == [[2.0, 0.0, 0.0, -2.0]]
+    # 2^24 + 1 is not a float32: the sum rounds to even (2^24); 2^24 + 3 rounds up to 2^24 + 4
+    fa = np.array([[16777216.0, 16777216.0, 0.1, -0.0]], dtype=np.float32)
+    fb = np.array([[1.0, 3.0, 0.2, 0.0]], dtype=np.float32)
+    got = orc.add_f32(fa, fb)
+    assert got.dtype == np.float32
+    assert got[0, 0] == 16777216.0 and got[0, 1] == 16777220.0
+    # float32(0.1) + float32(0.2) rounded to float32: 0x3E99999A (0.3 in float64 arithmetic
+    # would round to the same float32 here; the literal pins the bit pattern)
+    assert got[0, 2].view(np.uint32) == 0x3E99999A
+    assert got[0, 3] == 0.0
+    # mixed operands: a binary tensor counts as +-1.0
+    assert orc.add_f32(a, fb).tolist() == [[2.0, 4.0, np.float32(-1.0) + np.float32(0.2), -1.0]]
+
+
+def test_add_is_commutative_and_exact_against_float64_when_representable():
+    r = np.random.default_rng(5)
+    a = r.integers(-1000, 1000, size=(50, 70)).astype(np.float32)
+    b = r.integers(-1000, 1000, size=(50, 70)).astype(np.float32)
+    s = orc.add_f32(a, b)
+    assert np.array_equal(s, orc.add_f32(b, a))
+    assert np.array_equal(s.astype(np.float64), a.astype(np.float64) + b.astype(np.float64))
+
+
+def test_sage_layer_merged_by_addition_equals_the_concatenated_form():
+    """X_i W1 + agg W2 (merge by ADD) and [X_i | agg] [W1; W2] (merge by CONCAT) are the
+    same integers: pins the added form against the concatenated one, itself pinned above
+    to the two-matmul form."""
+    r = np.random.default_rng(11)
+    n, k, m = 300, 70, 33
+    src, dst = W.random_graph(r, n, 2000)
+    rp, col = orc.adjacency(src, dst, n, W.ADJ_SYMMETRIZE)
+    v = W.pm1(r, (n, k))
+    w = W.pm1(r, (2 * k, m))
+    t_agg = r.integers(-3, 4, size=k).astype(np.int32)
+    t_mm = r.integers(-9, 10, size=m).astype(np.int32)
+    cat = orc.sage_hidden_layer(rp, col, v, w, t_agg, t_mm)
+    added = orc.sage_hidden_layer_added(rp, col, v, w[:k], w[k:], t_agg, t_mm)
+    assert np.array_equal(cat, added)
+    # and the float route the ADD.FFF function takes: scaled products added in float32
+    nb = orc.rebin(orc.spmm_pm1(rp, col, v), t_agg)
+    z1, z2 = orc.bmm(v, w[:k]), orc.bmm(nb, w[k:])
+    y = orc.add_f32(z1.astype(np.float32), z2.astype(np.float32))      # small integers: exact
+    assert np.array_equal(orc.rebin_f32(y, t_mm.astype(np.float32)), cat)
