@@ -334,7 +334,9 @@ int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_ad
  * Errors: BITGNN_ERR_RANGE beyond the limits above (N, largest degree, C1, M), with the
  * limits in the message; BITGNN_ERR_INVALID_ARG / BITGNN_ERR_ALIGNMENT as elsewhere.
  * One fused call at a time per context (the barrier counter lives in the context); it is
- * asynchronous on `stream` like every other call.  All pointers are device pointers owned
+ * asynchronous on `stream` like every other call, allocates
+ * nothing, keeps no host state and is one kernel launch, so it may be recorded into a HIP
+ * graph and replayed.  All pointers are device pointers owned
  * by the caller. */
 /* Bound on the polls (~1 us each) of one wait at a barrier of bitgnn_gcn2_fused before
  * the wait is abandoned; default 2^22.  polls >= 1.  A tiny bound makes workgroups that

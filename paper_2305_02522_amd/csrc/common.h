@@ -18,7 +18,6 @@ struct bitgnn_ctx {
                           // (environment BITGNN_BGEMM=valu|mfma at context creation)
     uint32_t *queue;      // device words: [0] work counter of the blocked bit-SpMM,
                           // [kFusedBarrierWord] arrival counter of the fused kernel's barriers
-    uint32_t bar_base;    // value of that arrival counter once every launch so far has drained
     uint32_t fused_spin_limit; // polls of one barrier wait before it is abandoned
     char err[256];
     uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds

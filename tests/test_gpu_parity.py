@@ -808,6 +808,33 @@ def test_gcn2_fused_abandoned_wait_is_reported_and_recovered_from(B, ctx):
     adj.close()
 
 
+def test_gcn2_fused_replays_from_a_hip_graph(B, ctx):
+    """The one-launch model recorded into a HIP graph: every replay, with eager work and
+    synchronizations between the replays, gives the eager result."""
+    adj, rp, col, layers, x, model = _fused_case(B, ctx, 2708, 5300, (1433, 64, 7), SYM_LOOPS, 99,
+                                                 real_features=False)
+    want_logits, want_h = _check_fused(B, model, rp, col, layers, x)
+    xd = dev(x)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.forward_fused(xd)
+    for rep in range(4):
+        model.act[1].zero_()
+        model.logits.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(model.fused_status.item()) == 0
+        assert torch.equal(model.logits, want_logits), f"replay {rep}"
+        assert torch.equal(model.act[1], want_h), f"replay {rep}"
+        eager = model.forward(xd) if rep % 2 else model.forward_fused(xd)   # eager work between
+        torch.cuda.synchronize()
+        assert torch.equal(eager, want_logits)
+    del graph
+    adj.close()
+
+
 def test_gcn2_fused_rejects_what_it_cannot_run(B, ctx):
     """Outside its range the call fails before launching, naming the limits."""
     adj, rp, col, layers, x, model = _fused_case(B, ctx, 3000, 9000, (64, 64, 7), SYM_LOOPS, 77,
