@@ -187,6 +187,77 @@ def bench_spmm_f32(args, np, torch, B, ctx, adj, wl):
         "roofline": res["f32"]["roofline"], "bits_activations": res["bits"]}))
 
 
+def bench_gcn_full(args, np, torch, B, ctx, adj, wl):
+    """The two-layer GCN of the workload in the full-precision-aggregation recipe (products
+    binarized, aggregation in float32 over D^-1/2 A D^-1/2): BMM.FBF + BSpMM.FBB, then
+    BMM.BBF + BSpMM.FBF.  One JSON line; the roofline record is the first aggregation's
+    (float rows of the hidden width), the dominant kernel."""
+    assert wl.model == "gcn" and len(wl.layers) == 2, "--op gcn_full needs a two-layer GCN config"
+    n, nnz = wl.n, adj.nnz
+    k0, c1, m = (int(d) for d in wl.dims)
+    r = np.random.default_rng(7)
+    import ctypes
+    deg = torch.empty(n, dtype=torch.int32, device="cuda")
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    assert hip.hipMemcpy(deg.data_ptr(), adj.csr_pointers()[2], 4 * n, 3) == 0
+    dinv = (torch.clamp(deg.to(torch.float64), min=1.0) ** -0.5).to(torch.float32)
+    kw, mw = (k0 + 63) // 64, (c1 + 63) // 64
+    w1b = torch.zeros((c1, kw), dtype=torch.int64, device="cuda")
+    w2b = torch.zeros((m, mw), dtype=torch.int64, device="cuda")
+    B.pack_weights_i8(ctx, torch.as_tensor(wl.layers[0].w, device="cuda"), k0, c1, c1, w1b, kw)
+    B.pack_weights_i8(ctx, torch.as_tensor(wl.layers[1].w, device="cuda"), c1, m, m, w2b, mw)
+    a1 = torch.as_tensor(r.uniform(0.5, 1.5, size=c1).astype(np.float32), device="cuda")
+    a2 = torch.as_tensor(wl.layers[1].alpha, device="cuda")
+    tau = torch.as_tensor(r.standard_normal(c1).astype(np.float32), device="cuda")
+    x = torch.as_tensor(wl.x, device="cuda").to(torch.float32)
+    tmp1 = torch.empty((n, c1), dtype=torch.float32, device="cuda")
+    tmp2 = torch.empty((n, m), dtype=torch.float32, device="cuda")
+    h = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    logits = torch.empty((n, m), dtype=torch.float32, device="cuda")
+    marks = []
+
+    def step(timed):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        B.gcn_layer_full_f32(ctx, adj, x, k0, k0, None, w1b, c1, kw, a1, dinv, dinv, tau, tmp1, h,
+                             mw)
+        ev[1].record()
+        B.gcn_out_layer_weighted(ctx, adj, h, mw, c1, mw, w2b, m, mw, a2, dinv, dinv, tmp2,
+                                 logits, m)
+        ev[2].record()
+        if timed:
+            marks.append(ev)
+
+    for _ in range(max(1, args.warmup)):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    l1 = float(np.mean([e[0].elapsed_time(e[1]) for e in marks]))
+    l2 = float(np.mean([e[1].elapsed_time(e[2]) for e in marks]))
+    work = n * k0 * c1 + nnz * c1 + n * c1 * m + nnz * m
+    alg = nnz * 8 + n * (4 * c1 + 8 * mw + 12)          # ids + factors, float rows in, bits out
+    log(f"gcn_full: {ms:.3f} ms per model (layer 1 {l1:.3f} ms, layer 2 {l2:.3f} ms)")
+    print(json.dumps({
+        "metric": "binary GNN, full-precision aggregation recipe (G edge-channel + node-feature "
+                  "MAC/s) + full-graph inference ms, 1 GPU",
+        "value": round(work / ms / 1e6, 1), "unit": "G MAC/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 aggregation / u64 bit-packed products",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{args.config} {wl.name}: 2-layer GCN, full-precision "
+                               f"aggregation, N={n}, nnz={nnz}, dims={wl.dims}",
+                   "layer_ms": [round(l1, 4), round(l2, 4)]},
+        "roofline": {"kernel": "spmm_f32_kernel", "op": "L0 aggregation (float rows)",
+                     "bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": None, "traffic": None, "alg_MB": round(alg / 1e6, 2),
+                     "note": "bench.py --op spmm_f32 times this kernel alone"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,9 +271,10 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="time the layer calls even where the one-launch kernel applies "
                     "(two-layer GCN on a small graph, e.g. --config 1)")
-    ap.add_argument("--op", choices=["model", "spmm_f32"], default="model",
+    ap.add_argument("--op", choices=["model", "spmm_f32", "gcn_full"], default="model",
                     help="model: the binary GNN forward pass (the headline metric); spmm_f32: "
-                    "the symmetric-normalised full-precision aggregation on the same graph")
+                    "the symmetric-normalised full-precision aggregation on the same graph; "
+                    "gcn_full: the two-layer GCN with full-precision aggregation")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -231,6 +303,8 @@ def main():
         f"blocked={adj.blocked_info()}")
     if args.op == "spmm_f32":
         return bench_spmm_f32(args, np, torch, B, ctx, adj, wl)
+    if args.op == "gcn_full":
+        return bench_gcn_full(args, np, torch, B, ctx, adj, wl)
     model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
     x = torch.as_tensor(wl.x, device="cuda").to(torch.float32)
     torch.cuda.synchronize()

@@ -307,6 +307,26 @@ int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_ad
                                   int64_t w_stride, const float *alpha, const float *r,
                                   const float *f, float *tmp_f32, float *logits, int64_t ldo);
 
+/* GCN hidden layer with full-precision aggregation (Table 3's "Ours (full)" recipe, the
+ * aggregation of Bi-GCN: products binarized, aggregation not), BMM.xBF + BSpMM.FBB:
+ *   z = alpha .* (xbits W)  (float);  out = (r .* (A_hat (f .* z)) >= tau_agg).
+ * alpha: float [M] scale of the product;  r, f: float [N] or NULL (= 1);  tau_agg: float
+ * [M] (the BatchNorm + BIN after the aggregation, folded);  tmp_f32: caller scratch float
+ * [N][M] for z.  The float sum is bitgnn_spmm_f32's (step-rounded, reproducible). */
+int bitgnn_gcn_layer_full(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                          const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
+                          const uint64_t *wbits, int32_t M, int64_t w_stride, const float *alpha,
+                          const float *r, const float *f, const float *tau_agg, float *tmp_f32,
+                          uint64_t *out_bits, int64_t out_stride);
+/* The same on float features (BMM.FBF + BSpMM.FBB): x float [N][ldx], binarized by
+ * x >= tau_in[k] (tau_in NULL: x >= 0) inside the product. */
+int bitgnn_gcn_layer_full_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                              const float *x, int32_t K, int64_t ldx, const float *tau_in,
+                              const uint64_t *wbits, int32_t M, int64_t w_stride,
+                              const float *alpha, const float *r, const float *f,
+                              const float *tau_agg, float *tmp_f32, uint64_t *out_bits,
+                              int64_t out_stride);
+
 /* ---- whole model in one launch (Section 3.3: the end-to-end fused kernel) - */
 
 /* Range of bitgnn_gcn2_fused (larger inputs are not launch-bound: use the layer calls). */

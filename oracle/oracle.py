@@ -286,6 +286,17 @@ def gcn_hidden_layer_norm(rowptr, col, v, w, t_mm, r, f, tau_agg) -> np.ndarray:
     return rebin_f32(spmm_weighted_f32(rowptr, col, h, r, f), tau_agg)
 
 
+def gcn_hidden_layer_full(rowptr, col, v, w, alpha, r, f, tau_agg) -> np.ndarray:
+    """GCN hidden layer with full-precision aggregation (Table 3's "Ours (full)", the
+    aggregation of Bi-GCN-1 in Section 3.1): z = alpha * (v W) in float32 (BMM + SCL), then
+    out = bin_{tau}(diag(r) A_hat diag(f) z), the weighted sum in float32, step by step."""
+    n = v.shape[0]
+    z = np.empty((n, w.shape[1]), dtype=np.float32)
+    for lo in range(0, n, _CHUNK):
+        z[lo:lo + _CHUNK] = scale(bmm(v[lo:lo + _CHUNK], w), alpha)
+    return rebin_f32(spmm_weighted_f32(rowptr, col, z, r, f), tau_agg)
+
+
 def gcn_out_layer_norm(rowptr, col, v, w, alpha, r, f) -> np.ndarray:
     """Z = v W (integers);  logits = diag(r) A_hat diag(f) (alpha * Z): the output layer with
     a weighted adjacency; BMM.BBF with its scale, then the full-precision weighted

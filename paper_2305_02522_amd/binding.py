@@ -83,6 +83,10 @@ _SIGNATURES = {
                                              _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_sage_layer_weighted": (_int, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i64, _vp, _vp,
                                           _vp, _vp, _vp, _i64]),
+    "bitgnn_gcn_layer_full": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp,
+                                     _vp, _vp, _vp, _vp, _vp, _i64]),
+    "bitgnn_gcn_layer_full_f32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _i32, _i64,
+                                         _vp, _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_ctx_set_fused_spin_limit": (_int, [_vp, _u32]),
     "bitgnn_gcn2_fused": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _i32, _i64, _vp, _vp, _vp,
                                  _i32, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
@@ -304,6 +308,22 @@ def gcn_out_layer_weighted(ctx: Context, adj, xbits, x_stride, K, kwords, wbits,
         ctx.handle, _stream(), adj.handle if adj else None, _ptr(xbits), x_stride, K, kwords,
         _ptr(wbits), M, w_stride, _ptr(alpha), _ptr(r), _ptr(f), _ptr(tmp_f32), _ptr(logits),
         ldo))
+
+
+def gcn_layer_full(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_stride, alpha, r,
+                   f, tau_agg, tmp_f32, out_bits, out_stride):
+    ctx.check(_lib.bitgnn_gcn_layer_full(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(xbits), x_stride, K, kwords,
+        _ptr(wbits), M, w_stride, _ptr(alpha), _ptr(r), _ptr(f), _ptr(tau_agg), _ptr(tmp_f32),
+        _ptr(out_bits), out_stride))
+
+
+def gcn_layer_full_f32(ctx: Context, adj, x, K, ldx, tau_in, wbits, M, w_stride, alpha, r, f,
+                       tau_agg, tmp_f32, out_bits, out_stride):
+    ctx.check(_lib.bitgnn_gcn_layer_full_f32(
+        ctx.handle, _stream(), adj.handle if adj else None, _ptr(x), K, ldx, _ptr(tau_in),
+        _ptr(wbits), M, w_stride, _ptr(alpha), _ptr(r), _ptr(f), _ptr(tau_agg), _ptr(tmp_f32),
+        _ptr(out_bits), out_stride))
 
 
 def sage_layer_weighted(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, r, f, tau_agg,

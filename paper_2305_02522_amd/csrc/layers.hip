@@ -261,3 +261,72 @@ extern "C" int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, cons
     return bg_launch_spmm_f32(ctx, s, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_SCALE_F32, nullptr,
                               logits, ldo);
 }
+
+// GCN hidden layer of the full-precision-aggregation recipe (Table 3's "Ours (full)": the
+// products are binarized, the aggregation is not): BMM.xBF with its scale writes float rows
+// into the caller's scratch, BSpMM.FBB aggregates them over the weighted adjacency
+// diag(r) A_hat diag(f) in floats and binarizes the result with float thresholds (the
+// BatchNorm + BIN that follow, folded).
+static int gcn_layer_full_tail(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                               const float *tmp_f32, int32_t M, const float *r, const float *f,
+                               const float *tau_agg, uint64_t *out_bits, int64_t out_stride)
+{
+    return bg_launch_spmm_f32(ctx, s, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_THRESH_BITS,
+                              tau_agg, out_bits, out_stride);
+}
+
+extern "C" int bitgnn_gcn_layer_full(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                     const uint64_t *xbits, int64_t x_stride, int32_t K,
+                                     int32_t kwords, const uint64_t *wbits, int32_t M,
+                                     int64_t w_stride, const float *alpha, const float *r,
+                                     const float *f, const float *tau_agg, float *tmp_f32,
+                                     uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_layer_full: adj is null");
+    const int64_t n = adj->n;
+    int rc = bg_check_bgemm(ctx, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                            BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_spmm_f32(ctx, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_THRESH_BITS, tau_agg,
+                           out_bits, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                         BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    return gcn_layer_full_tail(ctx, s, adj, tmp_f32, M, r, f, tau_agg, out_bits, out_stride);
+}
+
+extern "C" int bitgnn_gcn_layer_full_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                         const float *x, int32_t K, int64_t ldx,
+                                         const float *tau_in, const uint64_t *wbits, int32_t M,
+                                         int64_t w_stride, const float *alpha, const float *r,
+                                         const float *f, const float *tau_agg, float *tmp_f32,
+                                         uint64_t *out_bits, int64_t out_stride)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, adj, BITGNN_ERR_INVALID_ARG, "bitgnn_gcn_layer_full_f32: adj is null");
+    const int64_t n = adj->n;
+    int rc = bg_check_bgemm_f32(ctx, x, n, K, ldx, tau_in, wbits, M, w_stride,
+                                BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    rc = bg_check_spmm_f32(ctx, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_THRESH_BITS, tau_agg,
+                           out_bits, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    hipStream_t s = (hipStream_t)stream;
+    rc = bg_launch_bgemm_f32(ctx, s, x, n, K, ldx, tau_in, wbits, M, w_stride,
+                             BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    return gcn_layer_full_tail(ctx, s, adj, tmp_f32, M, r, f, tau_agg, out_bits, out_stride);
+}

@@ -696,6 +696,54 @@ def test_weighted_layers(B, ctx, n, e, K, M):
     adj.close()
 
 
+@pytest.mark.parametrize("n,e,K,M,classes", [(300, 2500, 70, 40, 7), (4000, 60000, 128, 128, 41),
+                                             (3000, 20000, 1433, 64, 7)])
+def test_full_precision_aggregation_model(B, ctx, n, e, K, M, classes):
+    """The "Ours (full)" recipe end to end: BMM.FBF + BSpMM.FBB on float features, then
+    BMM.BBF + BSpMM.FBF, over the symmetrically normalised adjacency; and the hidden layer
+    on packed input.  Bits exact, logits within the float32 bound of the float64 sum."""
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, 900 + n)
+    x = r.standard_normal((n, K)).astype(np.float32)
+    v0 = orc.bin_f32(x)
+    w1, w2 = W.pm1(r, (K, M)), W.pm1(r, (M, classes))
+    a1 = r.uniform(0.5, 1.5, size=M).astype(np.float32)
+    a2 = r.uniform(0.5, 1.5, size=classes).astype(np.float32)
+    dinv = (orc.degrees(rp).astype(np.float64) ** -0.5).astype(np.float32)
+    tau = (r.standard_normal(M) * 2).astype(np.float32)
+    want_h = orc.gcn_hidden_layer_full(rp, col, v0, w1, a1, dinv, dinv, tau)
+    want_logits = orc.gcn_out_layer_norm(rp, col, want_h, w2, a2, dinv, dinv)
+
+    kw, mw = (K + 63) // 64, (M + 63) // 64
+    w1b = torch.zeros((M, kw), dtype=torch.int64, device="cuda")
+    B.pack_weights_i8(ctx, dev(w1), K, M, M, w1b, kw)
+    w2b = torch.zeros((classes, mw), dtype=torch.int64, device="cuda")
+    B.pack_weights_i8(ctx, dev(w2), M, classes, classes, w2b, mw)
+    tmp = torch.empty((n, M), dtype=torch.float32, device="cuda")
+    h = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    dv = dev(dinv)
+    B.gcn_layer_full_f32(ctx, adj, dev(x), K, K, None, w1b, M, kw, dev(a1), dv, dv, dev(tau), tmp,
+                         h, mw)
+    tmp2 = torch.empty((n, classes), dtype=torch.float32, device="cuda")
+    logits = torch.empty((n, classes), dtype=torch.float32, device="cuda")
+    B.gcn_out_layer_weighted(ctx, adj, h, mw, M, mw, w2b, classes, mw, dev(a2), dv, dv, tmp2,
+                             logits, classes)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(h), orc.to_words(want_h))
+    assert np.array_equal(logits.cpu().numpy().view(np.uint32), want_logits.view(np.uint32))
+    # the same hidden layer from packed input (BMM.BBF + BSpMM.FBB)
+    xb = dev(orc.to_words(v0).view(np.int64))
+    h2 = torch.zeros((n, mw + 1), dtype=torch.int64, device="cuda")
+    B.gcn_layer_full(ctx, adj, xb, kw, K, kw, w1b, M, kw, dev(a1), dv, dv, dev(tau), tmp, h2,
+                     mw + 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(h2)[:, :mw], orc.to_words(want_h))
+    with pytest.raises(B.BitgnnError) as e:
+        B.gcn_layer_full(ctx, adj, xb, kw, K, kw, w1b, M, kw, None, dv, dv, dev(tau), tmp, h2,
+                         mw + 1)
+    assert e.value.code == B.ERR_INVALID_ARG
+    adj.close()
+
+
 def test_forward_ops_equals_forward(B, ctx):
     for cfg, kw in ((4, {"n": 6000, "mean_deg": 120.0}), (3, {"n": 20000})):
         wl = W.make_workload(cfg, **kw)

@@ -538,3 +538,45 @@ def test_sage_layer_merged_by_addition_equals_the_concatenated_form():
     z1, z2 = orc.bmm(v, w[:k]), orc.bmm(nb, w[k:])
     y = orc.add_f32(z1.astype(np.float32), z2.astype(np.float32))      # small integers: exact
     assert np.array_equal(orc.rebin_f32(y, t_mm.astype(np.float32)), cat)
+
+
+# ---------------------------------------------------------------------------
+# full-precision aggregation recipe (Table 3, "Ours (full)")
+# ---------------------------------------------------------------------------
+
+def test_full_precision_aggregation_layer_special_cases():
+    """(1) Unit scale, unit factors, integer thresholds: the float layer is the integer layer
+    (all values are small integers, exact in float32).  (2) The redundant-scale remark of
+    Section 3.1.1: a positive scale in front of BIN changes nothing -- with power-of-two
+    scales (exact in float32) and thresholds scaled alike the bits are identical.  (3) The
+    weighted case against the float64 definition away from the thresholds."""
+    r = np.random.default_rng(21)
+    n, k, m = 400, 90, 37
+    src, dst = W.random_graph(r, n, 3000)
+    rp, col = orc.adjacency(src, dst, n, W.ADJ_SYMMETRIZE | W.ADJ_ADD_SELF_LOOPS)
+    v = W.pm1(r, (n, k))
+    w = W.pm1(r, (k, m))
+    t = r.integers(-40, 41, size=m).astype(np.int32)
+    ones = np.ones(m, dtype=np.float32)
+    # (1): no binarization between product and aggregation: out = (A (v W) >= t)
+    want = orc.rebin(orc.spmm_i64(rp, col, orc.bmm(v, w)), t)
+    got = orc.gcn_hidden_layer_full(rp, col, v, w, ones, None, None, t.astype(np.float32))
+    assert np.array_equal(got, want)
+    # (2): per-channel positive power-of-two scales
+    alpha = (2.0 ** r.integers(-3, 4, size=m)).astype(np.float32)
+    got2 = orc.gcn_hidden_layer_full(rp, col, v, w, alpha, None, None,
+                                     alpha * t.astype(np.float32))
+    assert np.array_equal(got2, want)
+    # (3): symmetric normalisation, float64 definition; entries within the float32 error
+    # bound of their threshold are not compared
+    deg = orc.degrees(rp).astype(np.float64)
+    dinv = deg ** -0.5
+    z64 = orc.bmm(v, w).astype(np.float64) * alpha.astype(np.float64)
+    y64 = orc.spmm_weighted(rp, col, z64, dinv, dinv)
+    tau = r.standard_normal(m).astype(np.float32)
+    got3 = orc.gcn_hidden_layer_full(rp, col, v, w, alpha, dinv.astype(np.float32),
+                                     dinv.astype(np.float32), tau)
+    mag = orc.spmm_weighted(rp, col, np.abs(z64), dinv, dinv)
+    safe = np.abs(y64 - tau) > (deg[:, None] + 6) * 2.0 ** -23 * mag + 1e-30
+    assert safe.mean() > 0.9
+    assert np.array_equal(got3[safe], np.where(y64 >= tau, 1, -1).astype(np.int8)[safe])
