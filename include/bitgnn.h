@@ -240,6 +240,16 @@ int bitgnn_add(bitgnn_ctx *ctx, void *stream, const void *a, int a_is_bits, int6
                const void *b, int b_is_bits, int64_t ldb, int64_t n, int32_t C, int epilogue,
                const float *tau, void *out, int64_t ldo);
 
+/* The same aggregation on the output of a BMM kept as integers with its scale (BMM + SCL
+ * feeding a full-precision BSpMM): x[j][c] = alpha[c] * (float)z[j][c], one rounded
+ * multiply -- the value the BMM's SCALE_F32 epilogue stores -- then as bitgnn_spmm_f32 with
+ * float rows; the result is identical to scaling first and aggregating the floats, from
+ * half the gathered bytes.  z: int16 [N][ldz] (ldz in int16 elements), 4-byte aligned;
+ * alpha: float [C].  Other arguments, epilogues and errors as bitgnn_spmm_f32. */
+int bitgnn_spmm_i16(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const int16_t *z,
+                    int32_t C, int64_t ldz, const float *alpha, const float *r, const float *f,
+                    int epilogue, const float *tau, void *out, int64_t ldo);
+
 /* ---- layers (Section 3.1.2 high-level functions; Table 3 caption recipe) - */
 
 /* GCN hidden layer, BMM.xBB + BSpMM.BBB:
@@ -300,7 +310,8 @@ int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *
 /* GCN output layer with the weighted adjacency:
  *   logits = r .* (A_hat (f .* (alpha .* (xbits W)))),
  * BMM.BBF with its scale, then the full-precision weighted aggregation.
- * tmp_f32: caller scratch float [N][M].  Other arguments as in bitgnn_gcn_out_layer. */
+ * tmp_f32: caller scratch of N*M floats (contents unspecified afterwards).  Other
+ * arguments as in bitgnn_gcn_out_layer. */
 int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                                   const uint64_t *xbits, int64_t x_stride, int32_t K,
                                   int32_t kwords, const uint64_t *wbits, int32_t M,
@@ -311,8 +322,9 @@ int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_ad
  * aggregation of Bi-GCN: products binarized, aggregation not), BMM.xBF + BSpMM.FBB:
  *   z = alpha .* (xbits W)  (float);  out = (r .* (A_hat (f .* z)) >= tau_agg).
  * alpha: float [M] scale of the product;  r, f: float [N] or NULL (= 1);  tau_agg: float
- * [M] (the BatchNorm + BIN after the aggregation, folded);  tmp_f32: caller scratch float
- * [N][M] for z.  The float sum is bitgnn_spmm_f32's (step-rounded, reproducible). */
+ * [M] (the BatchNorm + BIN after the aggregation, folded);  tmp_f32: caller scratch of
+ * N*M floats (holds the product as int16 rows when K <= 32767, as float rows otherwise).
+ * The float sum is bitgnn_spmm_f32's (step-rounded, reproducible). */
 int bitgnn_gcn_layer_full(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
                           const uint64_t *xbits, int64_t x_stride, int32_t K, int32_t kwords,
                           const uint64_t *wbits, int32_t M, int64_t w_stride, const float *alpha,

@@ -68,6 +68,7 @@ _SIGNATURES = {
     "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
     "bitgnn_spmm_f32": (_int, [_vp, _vp, _vp, _vp, _int, _i32, _i64, _vp, _vp, _int, _vp, _vp,
                                _i64]),
+    "bitgnn_spmm_i16": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _vp, _int, _vp, _vp, _i64]),
     "bitgnn_add": (_int, [_vp, _vp, _vp, _int, _i64, _vp, _int, _i64, _i64, _i32, _int, _vp, _vp,
                           _i64]),
     "bitgnn_gcn_layer": (_int, [_vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i64, _vp, _vp,
@@ -286,6 +287,12 @@ def gcn_out_layer(ctx: Context, adj, xbits, x_stride, K, kwords, wbits, M, w_str
     ctx.check(_lib.bitgnn_gcn_out_layer(ctx.handle, _stream(), adj.handle if adj else None,
                                         _ptr(xbits), x_stride, K, kwords, _ptr(wbits), M, w_stride,
                                         _ptr(alpha), _ptr(tmp_i32), _ptr(logits), ldo))
+
+
+def spmm_i16(ctx: Context, adj, z, C, ldz, alpha, r, f, epilogue, tau, out, ldo):
+    ctx.check(_lib.bitgnn_spmm_i16(ctx.handle, _stream(), adj.handle if adj else None, _ptr(z), C,
+                                   ldz, _ptr(alpha), _ptr(r), _ptr(f), epilogue, _ptr(tau),
+                                   _ptr(out), ldo))
 
 
 def add(ctx: Context, a, a_is_bits, lda, b, b_is_bits, ldb, n, C, epilogue, tau, out, ldo):

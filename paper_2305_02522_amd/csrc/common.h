@@ -202,7 +202,10 @@ int bg_check_spmm_f32(bitgnn_ctx *ctx, const bitgnn_adj *adj, const void *x, int
                       const float *tau, const void *out, int64_t ldo);
 int bg_launch_spmm_f32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const void *x,
                        int x_is_bits, int32_t C, int64_t ldx, const float *r, const float *f,
-                       int epilogue, const float *tau, void *out, int64_t ldo);
+                       int epilogue, const float *tau, void *out, int64_t ldo,
+                       const float *xscale);
+int bg_launch_narrow_rows(bitgnn_ctx *ctx, hipStream_t s, int32_t *z, int64_t n, int32_t M,
+                          int64_t ld32);
 int bg_check_bspmm(bitgnn_ctx *ctx, const bitgnn_adj *adj, const uint64_t *hbits, int32_t C,
                    int64_t h_stride, int epilogue, const int32_t *T, const void *out,
                    int64_t out_stride);

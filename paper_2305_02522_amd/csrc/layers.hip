@@ -162,6 +162,24 @@ extern "C" int bitgnn_sage_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn
                            BITGNN_EPI_SCALE_F32, nullptr, alpha, logits, ldo);
 }
 
+// Full-precision aggregation of a BMM's output alpha .* Z.  The float rows are not
+// materialised: the BMM leaves its raw integers (|z| <= K) in the caller's float scratch,
+// they are narrowed in place to int16 and the aggregation forms alpha_c * (float)z itself,
+// with the same single rounding as the BMM's scale epilogue -- the same bits from half the
+// gathered bytes, and the gathers are what bounds the aggregation.
+static const int32_t kNarrowMaxK = 32767;
+static int aggregate_scaled_integers(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
+                                     float *scratch, int32_t M, const float *alpha, const float *r,
+                                     const float *f, int epilogue, const float *tau, void *out,
+                                     int64_t ldo)
+{
+    int rc = bg_launch_narrow_rows(ctx, s, (int32_t *)scratch, adj->n, M, M);
+    if (rc != BITGNN_OK)
+        return rc;
+    return bg_launch_spmm_f32(ctx, s, adj, scratch, 0, M, 2 * (int64_t)M, r, f, epilogue, tau, out,
+                              ldo, alpha);
+}
+
 // The same two layers with a weighted adjacency, diag(r) A diag(f) (Section 3.1.1: a
 // weighted adjacency is the 0/1 matrix times its factorisation vectors): r = f = deg^-1/2
 // is the symmetric normalisation of GCN, r = 1/deg the mean aggregator of GraphSAGE.  The
@@ -194,7 +212,7 @@ extern "C" int bitgnn_gcn_layer_weighted(bitgnn_ctx *ctx, void *stream, const bi
     if (rc != BITGNN_OK)
         return rc;
     return bg_launch_spmm_f32(ctx, s, adj, tmp_bits, 1, M, mw, r, f, BITGNN_EPI_THRESH_BITS,
-                              tau_agg, out_bits, out_stride);
+                              tau_agg, out_bits, out_stride, nullptr);
 }
 
 extern "C" int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
@@ -223,7 +241,7 @@ extern "C" int bitgnn_sage_layer_weighted(bitgnn_ctx *ctx, void *stream, const b
     BG_NEED_DEVICE(ctx);
     hipStream_t s = (hipStream_t)stream;
     rc = bg_launch_spmm_f32(ctx, s, adj, cat_bits, 1, K_in, 2 * kw, r, f, BITGNN_EPI_THRESH_BITS,
-                            tau_agg, cat_bits + kw, 2 * kw);
+                            tau_agg, cat_bits + kw, 2 * kw, nullptr);
     if (rc != BITGNN_OK)
         return rc;
     return bg_launch_bgemm(ctx, s, cat_bits, n, 2 * kw, 2 * K_in, 2 * kw, wbits, M, w_stride,
@@ -254,12 +272,20 @@ extern "C" int bitgnn_gcn_out_layer_weighted(bitgnn_ctx *ctx, void *stream, cons
         return rc;
     BG_NEED_DEVICE(ctx);
     hipStream_t s = (hipStream_t)stream;
+    if (K <= kNarrowMaxK) {
+        rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                             BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_f32, M);
+        if (rc != BITGNN_OK)
+            return rc;
+        return aggregate_scaled_integers(ctx, s, adj, tmp_f32, M, alpha, r, f,
+                                         BITGNN_EPI_SCALE_F32, nullptr, logits, ldo);
+    }
     rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
                          BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
     if (rc != BITGNN_OK)
         return rc;
     return bg_launch_spmm_f32(ctx, s, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_SCALE_F32, nullptr,
-                              logits, ldo);
+                              logits, ldo, nullptr);
 }
 
 // GCN hidden layer of the full-precision-aggregation recipe (Table 3's "Ours (full)": the
@@ -272,7 +298,7 @@ static int gcn_layer_full_tail(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj 
                                const float *tau_agg, uint64_t *out_bits, int64_t out_stride)
 {
     return bg_launch_spmm_f32(ctx, s, adj, tmp_f32, 0, M, M, r, f, BITGNN_EPI_THRESH_BITS,
-                              tau_agg, out_bits, out_stride);
+                              tau_agg, out_bits, out_stride, nullptr);
 }
 
 extern "C" int bitgnn_gcn_layer_full(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
@@ -296,6 +322,14 @@ extern "C" int bitgnn_gcn_layer_full(bitgnn_ctx *ctx, void *stream, const bitgnn
         return rc;
     BG_NEED_DEVICE(ctx);
     hipStream_t s = (hipStream_t)stream;
+    if (K <= kNarrowMaxK) {
+        rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
+                             BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_f32, M);
+        if (rc != BITGNN_OK)
+            return rc;
+        return aggregate_scaled_integers(ctx, s, adj, tmp_f32, M, alpha, r, f,
+                                         BITGNN_EPI_THRESH_BITS, tau_agg, out_bits, out_stride);
+    }
     rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
                          BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
     if (rc != BITGNN_OK)
@@ -324,6 +358,14 @@ extern "C" int bitgnn_gcn_layer_full_f32(bitgnn_ctx *ctx, void *stream, const bi
         return rc;
     BG_NEED_DEVICE(ctx);
     hipStream_t s = (hipStream_t)stream;
+    if (K <= kNarrowMaxK) {
+        rc = bg_launch_bgemm_f32(ctx, s, x, n, K, ldx, tau_in, wbits, M, w_stride,
+                                 BITGNN_EPI_RAW_I32, nullptr, nullptr, tmp_f32, M);
+        if (rc != BITGNN_OK)
+            return rc;
+        return aggregate_scaled_integers(ctx, s, adj, tmp_f32, M, alpha, r, f,
+                                         BITGNN_EPI_THRESH_BITS, tau_agg, out_bits, out_stride);
+    }
     rc = bg_launch_bgemm_f32(ctx, s, x, n, K, ldx, tau_in, wbits, M, w_stride,
                              BITGNN_EPI_SCALE_F32, nullptr, alpha, tmp_f32, M);
     if (rc != BITGNN_OK)

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "bitgnn.h")).read()
     declared = set(re.findall(r"\b(bitgnn_[a-z0-9_]+)\s*\(", header))
-    assert len(declared) >= 28
+    assert len(declared) >= 29
     assert declared == set(B.EXPORTS)
     import ctypes
     lib = ctypes.CDLL(B.LIB_PATH)
@@ -98,6 +98,8 @@ def test_aggregation_and_layer_validation(vctx):
                  P8, 1) == B.ERR_INVALID_ARG
     assert _code(B.sage_out_layer, vctx, None, P8, 100, P8, 7, 4, P8, P8, P8, 7) == \
         B.ERR_INVALID_ARG
+    assert _code(B.spmm_i16, vctx, None, P8, 7, 8, P8, None, None, B.EPI_SCALE_F32, None, P8,
+                 7) == B.ERR_INVALID_ARG
     assert _code(B.gcn_layer_full, vctx, None, P8, 2, 100, 2, P8, 64, 2, P8, P8, P8, P8, P8, P8,
                  1) == B.ERR_INVALID_ARG
     assert _code(B.gcn_layer_full_f32, vctx, None, P8, 100, 100, None, P8, 64, 2, P8, P8, P8, P8,

@@ -439,6 +439,38 @@ def test_spmm_f32_variants(B, ctx, n, e, C, flags, hubs):
     adj.close()
 
 
+@pytest.mark.parametrize("n,e,C,hubs", [(1, 0, 1, 0), (300, 2500, 41, 0), (3000, 40000, 128, 1),
+                                        (5000, 30000, 300, 0)])
+def test_spmm_i16_scaled_integers(B, ctx, n, e, C, hubs):
+    """Aggregation of alpha .* z from int16 rows: bit for bit the aggregation of the float
+    rows the BMM's scale epilogue would have stored (the oracle scales, then sums)."""
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, 40 + n, hubs)
+    z = r.integers(-1500, 1501, size=(n, C)).astype(np.int16)
+    z[0, 0], z[-1, -1] = 32767, -32768
+    alpha = r.uniform(0.5, 1.5, size=C).astype(np.float32)
+    dinv = (orc.degrees(rp).astype(np.float64) ** -0.5).astype(np.float32)
+    want = orc.spmm_weighted_f32(rp, col, orc.scale(z.astype(np.int64), alpha), dinv, dinv)
+    ldz = C + 2 + (C & 1)                                     # padded, even
+    zd = dev(np.pad(z, ((0, 0), (0, ldz - C))))
+    out = torch.full((n, C + 1), 7.0, dtype=torch.float32, device="cuda")
+    B.spmm_i16(ctx, adj, zd, C, ldz, dev(alpha), dev(dinv), dev(dinv), B.EPI_SCALE_F32, None, out,
+               C + 1)
+    tau = (r.standard_normal(C) * 3).astype(np.float32)
+    cw = (C + 63) // 64
+    ob = torch.zeros((n, cw), dtype=torch.int64, device="cuda")
+    B.spmm_i16(ctx, adj, zd, C, ldz, dev(alpha), dev(dinv), dev(dinv), B.EPI_THRESH_BITS, dev(tau),
+               ob, cw)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:, :C].view(np.uint32), want.view(np.uint32))
+    assert np.all(got[:, C] == 7.0)
+    assert np.array_equal(words_np(ob), orc.to_words(orc.rebin_f32(want, tau)))
+    with pytest.raises(B.BitgnnError) as e:
+        B.spmm_i16(ctx, adj, zd, C, ldz, None, None, None, B.EPI_SCALE_F32, None, out, C + 1)
+    assert e.value.code == B.ERR_INVALID_ARG
+    adj.close()
+
+
 def test_spmm_f32_rejects_bad_arguments(B, ctx):
     adj, rp, col, r = _graph(B, ctx, 50, 200, SYM_LOOPS, 5)
     x = torch.zeros((50, 8), dtype=torch.float32, device="cuda")
@@ -697,7 +729,8 @@ def test_weighted_layers(B, ctx, n, e, K, M):
 
 
 @pytest.mark.parametrize("n,e,K,M,classes", [(300, 2500, 70, 40, 7), (4000, 60000, 128, 128, 41),
-                                             (3000, 20000, 1433, 64, 7)])
+                                             (3000, 20000, 1433, 64, 7),
+                                             (60, 300, 33000, 20, 3)])   # K > 32767: float rows
 def test_full_precision_aggregation_model(B, ctx, n, e, K, M, classes):
     """The "Ours (full)" recipe end to end: BMM.FBF + BSpMM.FBB on float features, then
     BMM.BBF + BSpMM.FBF, over the symmetrically normalised adjacency; and the hidden layer
