@@ -339,6 +339,28 @@ int bitgnn_gcn_layer_full_f32(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *a
                               const float *tau_agg, float *tmp_f32, uint64_t *out_bits,
                               int64_t out_stride);
 
+/* ---- tuning utilities (Section 3.4) --------------------------------------- */
+
+/* Type check of a chain of functions in the paper's notation (Section 3.1.2), e.g.
+ * "MM.FBB BSpMM.BBB MM.BBF BSpMM.FBF": names BMM / MM, BSpMM / SpMM, ADD, each with a
+ * three-letter suffix <input><second operand><output> of F (full precision) and B (binary);
+ * separators are spaces, ',', '+' or '>'.  The chain is well typed when every function's
+ * output precision is its successor's input precision, and the weight / adjacency operand
+ * of a BMM / BSpMM is B: then one variant may replace another.  Host-only; works on any
+ * context.  Returns BITGNN_OK, or BITGNN_ERR_INVALID_ARG with *bad_index (may be NULL) =
+ * position of the first offending function (0-based) and the reason in bitgnn_last_error. */
+int bitgnn_chain_check(bitgnn_ctx *ctx, const char *chain, int32_t *bad_index);
+
+/* Measures the two recipes of a GCN hidden layer of width K -> M on this graph, `reps`
+ * timed runs each after one untimed run, on scratch inputs of the right shape:
+ *   *bin_ms  <- BMM.BBB + BSpMM.BBB   (bitgnn_gcn_layer, binary aggregation)
+ *   *full_ms <- BMM.BBF + BSpMM.FBB   (bitgnn_gcn_layer_full, full-precision aggregation)
+ * in milliseconds per layer (host pointers, may be NULL).  The recipes differ in accuracy,
+ * so the choice stays with the caller.  Allocates and frees its scratch (about
+ * N * (K/8 + M/4 + 4 M) bytes) and synchronizes the stream: a set-up call. */
+int bitgnn_gcn_layer_tune(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, int32_t K,
+                          int32_t M, int32_t reps, float *bin_ms, float *full_ms);
+
 /* ---- whole model in one launch (Section 3.3: the end-to-end fused kernel) - */
 
 /* Range of bitgnn_gcn2_fused (larger inputs are not launch-bound: use the layer calls). */

@@ -88,6 +88,10 @@ _SIGNATURES = {
                                      _vp, _vp, _vp, _vp, _vp, _i64]),
     "bitgnn_gcn_layer_full_f32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _i32, _i64,
                                          _vp, _vp, _vp, _vp, _vp, _vp, _i64]),
+    "bitgnn_chain_check": (_int, [_vp, ctypes.c_char_p, ctypes.POINTER(_i32)]),
+    "bitgnn_gcn_layer_tune": (_int, [_vp, _vp, _vp, _i32, _i32, _i32,
+                                     ctypes.POINTER(ctypes.c_float),
+                                     ctypes.POINTER(ctypes.c_float)]),
     "bitgnn_ctx_set_fused_spin_limit": (_int, [_vp, _u32]),
     "bitgnn_gcn2_fused": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _vp, _i32, _i64, _vp, _vp, _vp,
                                  _i32, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
@@ -355,6 +359,26 @@ def sage_out_layer(ctx: Context, adj, cat_bits, K_in, wbits, M, w_stride, T_agg,
 
 
 FUSED_MAX_NODES, FUSED_MAX_DEGREE, FUSED_MAX_HIDDEN, FUSED_MAX_CLASSES = 65536, 1024, 256, 64
+
+
+def chain_check(ctx: Context, chain: str) -> int:
+    """-1 if the chain of functions is well typed, else the position of the first function
+    that is not (the reason is in ctx.last_error())."""
+    bad = _i32(-1)
+    rc = _lib.bitgnn_chain_check(ctx.handle, chain.encode(), ctypes.byref(bad))
+    if rc == OK:
+        return -1
+    if rc != ERR_INVALID_ARG or bad.value < 0:
+        ctx.check(rc)
+    return bad.value
+
+
+def gcn_layer_tune(ctx: Context, adj, K: int, M: int, reps: int = 3):
+    """(ms of the binary-aggregation layer, ms of the full-precision-aggregation layer)."""
+    a, b = ctypes.c_float(), ctypes.c_float()
+    ctx.check(_lib.bitgnn_gcn_layer_tune(ctx.handle, _stream(), adj.handle if adj else None, K, M,
+                                         reps, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def ctx_set_fused_spin_limit(ctx: Context, polls: int):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbitgnn.so")
-SOURCES = ["context.hip", "pack.hip", "add.hip", "bgemm.hip", "bgemm_mfma.hip", "adj_build.hip", "adj_blocked.hip", "bspmm.hip", "spmm_f32.hip", "fused_gcn.hip", "layers.hip"]
+SOURCES = ["context.hip", "pack.hip", "add.hip", "bgemm.hip", "bgemm_mfma.hip", "adj_build.hip", "adj_blocked.hip", "bspmm.hip", "spmm_f32.hip", "fused_gcn.hip", "layers.hip", "tune.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "bitgnn.h")).read()
     declared = set(re.findall(r"\b(bitgnn_[a-z0-9_]+)\s*\(", header))
-    assert len(declared) >= 29
+    assert len(declared) >= 31
     assert declared == set(B.EXPORTS)
     import ctypes
     lib = ctypes.CDLL(B.LIB_PATH)
@@ -116,6 +116,29 @@ def test_fused_spin_limit_validation(vctx):
     B.ctx_set_fused_spin_limit(vctx, 1)
     B.ctx_set_fused_spin_limit(vctx, 1 << 22)
     assert _code(B.ctx_set_fused_spin_limit, vctx, 0) == B.ERR_INVALID_ARG
+
+
+def test_chain_check_types_the_papers_recipes(vctx):
+    """The two recipes of Table 3's caption and the GCN pairs of Section 3.1.2 are well
+    typed; a precision mismatch, a full-precision weight operand and malformed names are
+    reported at their position."""
+    ok = ["MM.FBB + BSpMM.BBB + MM.BBF + BSpMM.FBF",          # binary aggregation
+          "BMM.FBF BSpMM.FBB BMM.BBF BSpMM.FBF",              # full-precision aggregation
+          "BMM.BBB,BSpMM.BBF", "BSpMM.BBB > ADD.BBF > BMM.FBB", "ADD.FFF"]
+    for chain in ok:
+        assert B.chain_check(vctx, chain) == -1, chain
+    assert B.chain_check(vctx, "MM.FBB BSpMM.FBB") == 1
+    assert "takes F but its predecessor produces B" in vctx.last_error()
+    assert B.chain_check(vctx, "BMM.FBB BSpMM.BBB BMM.FBF") == 2
+    assert B.chain_check(vctx, "BMM.FFB") == 0 and "weight" in vctx.last_error()
+    assert B.chain_check(vctx, "BMM.FBB BSpMM.BFB") == 1 and "adjacency" in vctx.last_error()
+    assert B.chain_check(vctx, "BMM.FBB CONV.BBB") == 1
+    assert B.chain_check(vctx, "BMM.FB") == 0
+    assert B.chain_check(vctx, "BMM.FBBB") == 0
+    assert B.chain_check(vctx, "BMM.FXB") == 0
+    with pytest.raises(B.BitgnnError):
+        B.chain_check(vctx, "  ")
+    assert _code(B.gcn_layer_tune, vctx, None, 64, 64, 3) == B.ERR_INVALID_ARG
 
 
 def test_ctx_create_rejects_bad_device():

@@ -372,6 +372,15 @@ def test_adj_tune_measures_both_kernels_and_keeps_results(B, ctx):
 
 
 # ------------------------------------------------------------------ a5: integer aggregation
+def test_gcn_layer_tune_measures_both_recipes(B, ctx):
+    adj, rp, col, r = _graph(B, ctx, 5000, 60000, SYM_LOOPS, 12)
+    bin_ms, full_ms = B.gcn_layer_tune(ctx, adj, 100, 70, reps=2)
+    assert 0.0 < bin_ms < 100.0 and 0.0 < full_ms < 100.0
+    with pytest.raises(B.BitgnnError):
+        B.gcn_layer_tune(ctx, adj, 100, 70, reps=0)
+    adj.close()
+
+
 @pytest.mark.parametrize("n,e,M", [(50, 200, 1), (1000, 9000, 7), (3000, 50000, 41),
                                    (500, 4000, 64), (300, 2000, 130)])
 def test_spmm_i32(B, ctx, n, e, M):
