@@ -106,25 +106,29 @@ __global__ __launch_bounds__(256) void spmm_f32_kernel(
                     wlo[u] = (uint32_t)w;
                     whi[u] = (uint32_t)(w >> 32);
                 }
-                for (uint32_t t = 0; t < cnt; ++t) {
-                    const float fj =
-                        __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fl), (int)t));
+                // one neighbour: its factor and words are read from its lane; a word, being
+                // the same for all lanes, serves as the lane mask that picks +f or -f (a
+                // tile past the last channel sums zero words and is never stored)
+                auto add_neighbour = [&](int t) {
+                    const float fj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fl), t));
 #pragma unroll
                     for (int u = 0; u < kTiles; ++u) {
-                        if (c0 + 64 * u >= C)
-                            continue;
                         const uint64_t word =
-                            (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)wlo[u], (int)t) |
-                            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)whi[u], (int)t)
-                             << 32);
+                            (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)wlo[u], t) |
+                            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)whi[u], t) << 32);
                         const float x = __builtin_amdgcn_inverse_ballot_w64(word) ? 1.0f : -1.0f;
                         acc[u] = acc[u] + mul_rounded(fj, x);
                     }
+                };
+                uint32_t t = 0;
+                for (; t + 4 <= cnt; t += 4) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        add_neighbour((int)t + q);
                 }
+                for (; t < cnt; ++t)
+                    add_neighbour((int)t);
             }
-            // kAhead neighbours per turn: their rows are requested together, then added in
-            // order (a turn past the end repeats the last neighbour and drops it; a tile
-            // past the last channel re-reads the last channel and is never stored)
             // The scalar unit is what limits narrow rows, so a neighbour costs it as little
             // as possible: the 64-bit row offset is computed once per lane for the block's
             // 64 neighbours and handed out by lane reads (lanes past the block's end repeat
