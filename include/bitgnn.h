@@ -387,7 +387,11 @@ int bitgnn_gcn_layer_tune(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, 
  *           exits; logits and h_bits are then undefined.  Never cleared by the library.
  * Errors: BITGNN_ERR_RANGE beyond the limits above (N, largest degree, C1, M), with the
  * limits in the message; BITGNN_ERR_INVALID_ARG / BITGNN_ERR_ALIGNMENT as elsewhere.
- * One fused call at a time per context (the barrier counter lives in the context); it is
+ * One fused call at a time per context (the barrier counter lives in the context), and no
+ * fused call of another context running at the same time on another stream: each grid
+ * waits inside the kernel for all of its workgroups, so two such grids can hold the compute
+ * units the other needs (the bounded waits then expire and *status says so).  Ordinary
+ * kernels on other streams only delay it.  The call is
  * asynchronous on `stream` like every other call, allocates
  * nothing, keeps no host state and is one kernel launch, so it may be recorded into a HIP
  * graph and replayed.  All pointers are device pointers owned
