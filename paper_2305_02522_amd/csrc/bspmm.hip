@@ -42,10 +42,9 @@ __device__ __forceinline__ void csa(uint32_t &acc, uint32_t b, uint32_t c, uint3
 
 // Seeds of the vertical counters: table[(e*P + p)*W32 + w] bit c' = bit p of
 // (BIAS - t(e, c)), c = 32 w + c', BIAS = 2^(P-1), t clamped to +-2^(P-2).
-__global__ void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C, int32_t W32, int P,
-                                  uint32_t *__restrict__ table)
+__device__ __forceinline__ void seed_entry(int idx, const int32_t *__restrict__ T, int32_t C,
+                                           int32_t W32, int P, uint32_t *__restrict__ table)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= 2 * P * W32)
         return;
     const int w = idx % W32;
@@ -63,6 +62,12 @@ __global__ void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C, int3
         word |= (uint32_t)((off >> p) & 1u) << b;
     }
     table[idx] = word;
+}
+
+__global__ void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C, int32_t W32, int P,
+                                  uint32_t *__restrict__ table)
+{
+    seed_entry(blockIdx.x * blockDim.x + threadIdx.x, T, C, W32, P, table);
 }
 
 // Epilogue of one (node, 32-channel word): `acc` holds the bit-sliced count (plus
@@ -302,13 +307,66 @@ __device__ __forceinline__ void blk_cascade(uint32_t (&acc)[PP][4], uint32_t (&p
     }
 }
 
+// Weights of the class projection as +-1 bytes, one 128-channel window of one class per
+// call (threads t < 128 of a workgroup; all threads of the workgroup must call), and the
+// column sums of the window.
+__device__ __forceinline__ void project_weights_entry(int c, int win, int t,
+                                                      const uint32_t *__restrict__ w32,
+                                                      int64_t w_stride32, int32_t K, int32_t M,
+                                                      int32_t Mpad, int8_t *__restrict__ w8,
+                                                      int32_t *__restrict__ wsum)
+{
+    const int k = win * 128 + t;
+    int v = 0;
+    if (t < 128 && c < M && k < K)
+        v = ((w32[(int64_t)c * w_stride32 + (k >> 5)] >> (k & 31)) & 1u) ? 1 : -1;
+    if (t < 128)
+        w8[((int64_t)win * Mpad + c) * 128 + t] = (int8_t)v;
+    // column sum: two wavefronts, combined through LDS
+    __shared__ int part[2];
+    int sum = v;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        sum += __shfl_xor(sum, d, 64);
+    if (t < 128 && (t & 63) == 0)
+        part[t >> 6] = sum;
+    __syncthreads();
+    if (t == 0)
+        wsum[win * Mpad + c] = part[0] + part[1];
+}
+
+// Set-up work that rides along with the first permute launch of a call instead of taking
+// a launch of its own: the threshold seeds of the merge, or the projection's weights.
+struct PermuteAux {
+    int kind; // 0 none, 1 seeds, 2 projection weights
+    // seeds
+    const int32_t *T;
+    int32_t C, W32, P;
+    uint32_t *table;
+    // projection weights
+    const uint32_t *w32;
+    int64_t w_stride32;
+    int32_t K, M, Mpad, nwin;
+    int8_t *w8;
+    int32_t *wsum;
+};
+
 // Activation rows in degree order (one 128-channel window); also rewinds the work
 // counter of the aggregation kernel that follows on the same stream.
-__global__ void blk_permute_kernel(const uint32_t *__restrict__ h32, int64_t h_stride32,
-                                   const int32_t *__restrict__ order, uint32_t n, int w0,
-                                   int W32, uint4 *__restrict__ hperm,
-                                   uint32_t *__restrict__ queue)
+__global__ __launch_bounds__(256) void blk_permute_kernel(
+    const uint32_t *__restrict__ h32, int64_t h_stride32, const int32_t *__restrict__ order,
+    uint32_t n, int w0, int W32, uint4 *__restrict__ hperm, uint32_t *__restrict__ queue,
+    uint32_t permute_blocks, PermuteAux aux)
 {
+    if (blockIdx.x >= permute_blocks) { // workgroup-uniform: the set-up work's own workgroups
+        const int vb = (int)(blockIdx.x - permute_blocks);
+        if (aux.kind == 1)
+            seed_entry(vb * 256 + (int)threadIdx.x, aux.T, aux.C, aux.W32, aux.P, aux.table);
+        else if (aux.kind == 2)
+            project_weights_entry(vb % aux.Mpad, vb / aux.Mpad, (int)threadIdx.x, aux.w32,
+                                  aux.w_stride32, aux.K, aux.M, aux.Mpad, aux.w8, aux.wsum);
+        return;
+    }
     const uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x;
     if (slot == 0)
         *queue = 0u;
@@ -688,32 +746,6 @@ __global__ __launch_bounds__(kBlock) void bspmm_merge_kernel(
 //   result: lane = node + 16 * g     holds classes 16 tile + 4 g + (0..3)
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-// +-1 bytes of the class weights per window of 128 channels (0 beyond K or M), class rows
-// padded to a multiple of 16, plus the column sums of every window; written per call
-// into the workspace (a few KB).  Layout: w8[(win * Mpad + c) * 128 + k], wsum[win * Mpad + c].
-__global__ void project_weights_kernel(const uint32_t *__restrict__ w32, int64_t w_stride32,
-                                       int32_t K, int32_t M, int32_t Mpad,
-                                       int8_t *__restrict__ w8, int32_t *__restrict__ wsum)
-{
-    const int c = blockIdx.x, win = blockIdx.y, t = threadIdx.x; // 128 threads
-    const int k = win * 128 + t;
-    int v = 0;
-    if (c < M && k < K)
-        v = ((w32[(int64_t)c * w_stride32 + (k >> 5)] >> (k & 31)) & 1u) ? 1 : -1;
-    w8[((int64_t)win * Mpad + c) * 128 + t] = (int8_t)v;
-    // column sum: two wavefronts, combined through LDS
-    __shared__ int part[2];
-    int sum = v;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1)
-        sum += __shfl_xor(sum, d, 64);
-    if ((t & 63) == 0)
-        part[t >> 6] = sum;
-    __syncthreads();
-    if (t == 0)
-        wsum[win * Mpad + c] = part[0] + part[1];
-}
-
 // 8x8 bit transpose of the 64-bit matrix (hi:lo), row r = byte r: three delta swaps.
 __device__ __forceinline__ void transpose8x8(uint32_t &lo, uint32_t &hi)
 {
@@ -1001,6 +1033,22 @@ static int planes_for(const bitgnn_adj *adj)
     return P;
 }
 
+// Permute launch of one 128-channel window; `aux` (first window only) adds the workgroups
+// of the call's set-up work.
+static void launch_permute(hipStream_t s, const bitgnn_adj *adj, const uint32_t *h32,
+                           int64_t h_stride32, int w0, int W32, uint4 *hperm, uint32_t *queue,
+                           const PermuteAux &aux)
+{
+    const unsigned pb = (unsigned)((adj->n + 255) / 256);
+    unsigned extra = 0;
+    if (aux.kind == 1)
+        extra = (unsigned)((2 * aux.P * aux.W32 + 255) / 256);
+    else if (aux.kind == 2)
+        extra = (unsigned)(aux.Mpad * aux.nwin);
+    blk_permute_kernel<<<pb + extra, 256, 0, s>>>(h32, h_stride32, adj->order, (uint32_t)adj->n, w0,
+                                                  W32, hperm, queue, pb, aux);
+}
+
 static int launch_seeds(bitgnn_ctx *ctx, hipStream_t s, int epilogue, const int32_t *T, int32_t C,
                         int32_t W32, int P, const uint32_t **seeds)
 {
@@ -1023,21 +1071,31 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     const bitgnn_blocked *b = adj->blk;
     const int32_t W32 = (C + 31) / 32;
     const int P = planes_for(adj);
-    const uint32_t *seeds;
-    int rc = launch_seeds(ctx, s, epilogue, T, C, W32, P, &seeds);
-    if (rc != BITGNN_OK)
-        return rc;
+    // the threshold seeds are computed by extra workgroups of the first permute launch
+    PermuteAux aux{};
+    const uint32_t *seeds = nullptr;
+    if (epilogue == BITGNN_EPI_THRESH_BITS) {
+        BG_REQUIRE(ctx, (size_t)(2 * P * W32) <= ctx->seed_table_words, BITGNN_ERR_UNSUPPORTED,
+                   "bitgnn_bspmm: seed table too small");
+        aux.kind = 1;
+        aux.T = T;
+        aux.C = C;
+        aux.W32 = W32;
+        aux.P = P;
+        aux.table = ctx->seed_table;
+        seeds = ctx->seed_table;
+    }
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
     const size_t part_bytes = (size_t)b->n_vrows * part_planes_for(b) * 16;
-    rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
+    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
     if (rc != BITGNN_OK)
         return rc;
     uint4 *hperm = (uint4 *)ctx->ws;
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
     const uint32_t *h32 = (const uint32_t *)hbits;
     for (int win = 0; win * 4 < W32; ++win) {
-        blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
-            h32, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32, hperm, ctx->queue);
+        launch_permute(s, adj, h32, h_stride * 2, win * 4, W32, hperm, ctx->queue,
+                       win == 0 ? aux : PermuteAux{});
         rc = launch_blk(ctx, s, adj, hperm, partial);
         if (rc != BITGNN_OK)
             return rc;
@@ -1085,18 +1143,26 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
     int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
     int32_t *wsum = (int32_t *)(w8 + w8_bytes);
-    project_weights_kernel<<<dim3(Mpad, nwin), 128, 0, s>>>((const uint32_t *)wbits, w_stride * 2,
-                                                            K, M, Mpad, w8, wsum);
-    BG_LAUNCH_CHECK(ctx, "project_weights");
+    // the projection's +-1 byte weights are produced by extra workgroups of the first
+    // permute launch
+    PermuteAux aux{};
+    aux.kind = 2;
+    aux.w32 = (const uint32_t *)wbits;
+    aux.w_stride32 = w_stride * 2;
+    aux.K = K;
+    aux.M = M;
+    aux.Mpad = Mpad;
+    aux.nwin = nwin;
+    aux.w8 = w8;
+    aux.wsum = wsum;
     const unsigned grid = (unsigned)((adj->n + kProjWaves * 16 - 1) / (kProjWaves * 16));
     // digits of 7 bits: max_degree < 2^(7 NB)
     int NB = 1;
     while ((1ll << (7 * NB)) <= adj->max_degree)
         ++NB;
     for (int win = 0; win < nwin; ++win) {
-        blk_permute_kernel<<<(unsigned)((adj->n + 255) / 256), 256, 0, s>>>(
-            (const uint32_t *)hbits, h_stride * 2, adj->order, (uint32_t)adj->n, win * 4, W32,
-            hperm, ctx->queue);
+        launch_permute(s, adj, (const uint32_t *)hbits, h_stride * 2, win * 4, W32, hperm,
+                       ctx->queue, win == 0 ? aux : PermuteAux{});
         rc = launch_blk(ctx, s, adj, hperm, partial);
         if (rc != BITGNN_OK)
             return rc;
