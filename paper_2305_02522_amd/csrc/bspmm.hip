@@ -131,21 +131,28 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
 
     const uint32_t *hw = h32 + w;
     uint32_t blk = 0; // blocks of 16 neighbours consumed so far (wave-uniform)
-    while (__ballot(e < end) != 0ull) {
-        // clamped, unconditional loads (masked afterwards): the 16 index loads and then
-        // the 16 gathers are in flight together instead of one at a time
-        uint32_t x[kGroup];
-        int32_t j[kGroup];
+    // clamped, unconditional loads (masked afterwards): the 16 index loads and then the 16
+    // gathers are in flight together instead of one at a time, and the indices of the next
+    // 16 neighbours are requested before this block's gathers are waited for, so that a long
+    // row pays one memory latency per block instead of two
+    const uint32_t last = deg ? end - 1 : 0u;
+    int32_t j[kGroup];
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u)
-            j[u] = col[e + u < end ? e + u : (deg ? end - 1 : 0u)];
+    for (int u = 0; u < kGroup; ++u)
+        j[u] = col[e + u < end ? e + u : last];
+    while (__ballot(e < end) != 0ull) {
+        uint32_t x[kGroup];
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) // lanes past their row end gather node 0 (always valid)
             x[u] = hw[(int64_t)(e + u < end ? j[u] : 0) * h_stride32];
+        const uint32_t e_next = (end - e > (uint32_t)kGroup) ? e + kGroup : end;
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u)
+            j[u] = col[e_next + u < end ? e_next + u : last];
 #pragma unroll
         for (int u = 0; u < kGroup; ++u)
             x[u] = e + u < end ? x[u] : 0u;
-        e = (end - e > (uint32_t)kGroup) ? e + kGroup : end;
+        e = e_next;
 
         // 16 words -> planes 0..3 plus one carry of weight 16
         uint32_t a2, b2, a4, b4, a8, b8, c16;
