@@ -146,6 +146,45 @@ def test_cfg4_weighted_aggregation_sampled_rows():
     say(f"cfg4: weighted aggregation checked on {len(rows)} rows, degrees up to {deg[rows].max()}")
 
 
+def test_cfg4_full_precision_aggregation_layer_sampled_rows():
+    """The hidden layer of the full-precision-aggregation recipe at full size (what
+    `bench.py --op gcn_full` times: float features, BMM kept as integers, aggregated from
+    int16 rows with the scale applied inside), on sampled output rows.  The oracle forms
+    z = alpha * (bin(x) W) for all nodes in float32 and sums the sampled rows step by step."""
+    from paper_2305_02522_amd import binding as B
+    r = _run(4)
+    wl = r.wl
+    n, K, M = wl.n, int(wl.dims[0]), int(wl.dims[1])
+    deg = orc.degrees(r.rp)
+    dinv = (np.maximum(deg, 1).astype(np.float64) ** -0.5).astype(np.float32)
+    rng = np.random.default_rng(6)
+    alpha = rng.uniform(0.5, 1.5, M).astype(np.float32)
+    tau = rng.uniform(-0.5, 0.5, M).astype(np.float32)
+    t = time.time()
+    v0 = orc.bin_f32(wl.x.astype(np.float32))
+    z = np.empty((n, M), dtype=np.float32)
+    step = 1 << 15
+    for lo in range(0, n, step):
+        z[lo:lo + step] = orc.scale(orc.bmm(v0[lo:lo + step], wl.layers[0].w), alpha)
+    say(f"cfg4: oracle scaled product in {time.time() - t:.0f}s")
+    kw, mw = (K + 63) // 64, (M + 63) // 64
+    wb = torch.zeros((M, kw), dtype=torch.int64, device="cuda")
+    B.pack_weights_i8(r.ctx, dev(wl.layers[0].w), K, M, M, wb, kw)
+    tmp = torch.empty((n, M), dtype=torch.float32, device="cuda")
+    h = torch.zeros((n, mw), dtype=torch.int64, device="cuda")
+    B.gcn_layer_full_f32(r.ctx, r.adj, dev(wl.x).to(torch.float32), K, K, None, wb, M, kw,
+                         dev(alpha), dev(dinv), dev(dinv), dev(tau), tmp, h, mw)
+    torch.cuda.synchronize()
+    got = words_np(h)
+    order = np.argsort(-deg, kind="stable")
+    rows = np.unique(np.concatenate([order[:8], order[-64:], rng.integers(0, n, 600)]))
+    for i in rows:
+        y = orc.spmm_weighted_f32(r.rp, r.col, z, dinv, dinv, rows=(int(i), int(i) + 1))
+        assert np.array_equal(got[i:i + 1], orc.to_words(orc.rebin_f32(y, tau))), \
+            f"row {i} (degree {deg[i]})"
+    say(f"cfg4: full-precision-aggregation layer checked on {len(rows)} rows")
+
+
 def test_cfg5_adjacency_and_layer0():
     r = _run(5)
     assert r.adj.nnz == r.rp[-1]
