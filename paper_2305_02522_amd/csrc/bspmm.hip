@@ -222,8 +222,20 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
     const uint32_t beg = rowptr[row], end = rowptr[row + 1];
     for (int c = li; c < M; c += (1 << lpr_log2)) {
         int32_t sum = 0;
-        for (uint32_t e = beg; e < end; ++e)
-            sum += Z[(int64_t)col[e] * z_stride + c];
+        // eight neighbours per turn: their indices, then their values, are in flight
+        // together (clamped loads; integer sums do not depend on the order)
+        for (uint32_t e = beg; e < end; e += 8) {
+            int32_t j[8], z[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                j[u] = col[e + u < end ? e + u : end - 1];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                z[u] = Z[(int64_t)j[u] * z_stride + c];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                sum += e + u < end ? z[u] : 0;
+        }
         if (SCALE)
             ((float *)out)[(int64_t)row * out_stride + c] = alpha[c] * (float)sum;
         else
