@@ -134,6 +134,36 @@ __global__ void rank_kernel(const int32_t *__restrict__ order, uint32_t N,
         rank[order[s]] = (int32_t)s;
 }
 
+// Segment counts of the rows in degree order (entry N is 0, so that the exclusive scan of
+// N + 1 entries ends with the total), and the number of rows with more than one segment
+// (they are the first ones of the order).
+__global__ void seg_count_kernel(const int32_t *__restrict__ order, const int32_t *__restrict__ deg,
+                                 uint32_t N, uint32_t seg_len, uint32_t *__restrict__ nseg,
+                                 uint32_t *__restrict__ n_long)
+{
+    const uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot > N)
+        return;
+    uint32_t c = 0;
+    if (slot < N) {
+        const uint32_t d = (uint32_t)deg[order[slot]];
+        c = d <= seg_len ? 1u : (d + seg_len - 1) / seg_len;
+        if (c > 1)
+            atomicMax(n_long, slot + 1);
+    }
+    nseg[slot] = c;
+}
+
+__global__ void seg_slot_kernel(const uint32_t *__restrict__ seg_ptr, uint32_t n_long,
+                                uint32_t *__restrict__ seg_slot)
+{
+    const uint32_t slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= n_long)
+        return;
+    for (uint32_t v = seg_ptr[slot]; v < seg_ptr[slot + 1]; ++v)
+        seg_slot[v] = slot;
+}
+
 __global__ void col_slot_kernel(const int32_t *__restrict__ col, uint32_t nnz,
                                 const int32_t *__restrict__ rank, int32_t *__restrict__ col_slot)
 {
@@ -284,6 +314,39 @@ extern "C" int bitgnn_adj_build(bitgnn_ctx *ctx, void *stream, const int32_t *sr
         adj->col_slot = (int32_t *)col_slot.release();
         adj->device_bytes += (size_t)nnz * 4;
     }
+    // segments of the long rows for the CSR bit-SpMM
+    if (N > 0) {
+        DevBuf nseg, seg_slot, cnt;
+        BG_HIP(ctx, nseg.alloc(((size_t)N + 1) * 4));
+        BG_HIP(ctx, cnt.alloc(4));
+        BG_HIP(ctx, hipMemsetAsync(cnt.p, 0, 4, s));
+        adj->seg_len = (int64_t)nnz >= kSegLargeNnz ? kSegLenLarge : kSegLenSmall;
+        seg_count_kernel<<<blocks_for(N + 1, 256), 256, 0, s>>>(
+            adj->order, adj->deg, (uint32_t)N, adj->seg_len, nseg.as<uint32_t>(),
+            cnt.as<uint32_t>());
+        BG_LAUNCH_CHECK(ctx, "seg_count");
+        DevBuf sws;
+        BG_HIP(ctx, sws.alloc(scan_ws_words((uint64_t)N + 1) * 4));
+        scan_inplace(nseg.as<uint32_t>(), (uint32_t)N + 1, sws.as<uint32_t>(), s);
+        uint32_t n_long = 0, n_long_segs = 0;
+        BG_HIP(ctx, hipMemcpyAsync(&n_long, cnt.p, 4, hipMemcpyDeviceToHost, s));
+        BG_HIP(ctx, hipStreamSynchronize(s));
+        if (n_long > 0) {
+            BG_HIP(ctx, hipMemcpyAsync(&n_long_segs, nseg.as<uint32_t>() + n_long, 4,
+                                       hipMemcpyDeviceToHost, s));
+            BG_HIP(ctx, hipStreamSynchronize(s));
+            BG_HIP(ctx, seg_slot.alloc((size_t)n_long_segs * 4));
+            seg_slot_kernel<<<blocks_for(n_long, 256), 256, 0, s>>>(nseg.as<uint32_t>(), n_long,
+                                                                   seg_slot.as<uint32_t>());
+            BG_LAUNCH_CHECK(ctx, "seg_slot");
+            BG_HIP(ctx, hipStreamSynchronize(s));
+            adj->seg_slot = (uint32_t *)seg_slot.release();
+            adj->seg_ptr = (uint32_t *)nseg.release(); // the first n_long + 1 entries are used
+            adj->device_bytes += ((size_t)N + 1) * 4 + (size_t)n_long_segs * 4;
+        }
+        adj->n_long = n_long;
+        adj->n_long_segs = n_long_segs;
+    }
     *out = adj;
     return BITGNN_OK;
 }
@@ -349,6 +412,8 @@ extern "C" void bitgnn_adj_destroy(bitgnn_adj *adj)
     (void)hipFree(adj->deg);
     (void)hipFree(adj->order);
     (void)hipFree(adj->col_slot);
+    (void)hipFree(adj->seg_ptr);
+    (void)hipFree(adj->seg_slot);
     bg_free_blocked(adj->blk);
     free(adj);
 }

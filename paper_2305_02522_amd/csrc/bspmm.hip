@@ -106,26 +106,57 @@ __device__ __forceinline__ void bspmm_epilogue(const uint32_t (&acc)[P], uint32_
     }
 }
 
+// The segments of the rows with more than seg_len neighbours, as the kernels see them.
+struct RowSegments {
+    const uint32_t *seg_ptr;  // [n_long + 1] first segment of long row (by degree-order slot)
+    const uint32_t *seg_slot; // [n_long_segs] slot of a segment's row
+    uint32_t n_long, n_long_segs;
+    uint32_t seg_len;  // neighbours per segment
+    int planes;        // planes of a segment's count: seg_len < 2^planes (at most 12)
+    uint32_t *partial; // [n_long_segs][planes][W32] bit-sliced counts of the segments
+};
+static_assert(kSegLenLarge < (1u << 12), "every kernel variant has at least 12 planes");
+
+// A thread group of W32 lanes walks one "virtual row": a segment of at most seg_len
+// neighbours of a long row (those come first, and leave their bit-sliced counts in
+// `seg.partial` for bspmm_long_rows_kernel), or a whole row of at most seg_len neighbours,
+// finished here.  Without the split the longest row of a power-law graph, walked serially at
+// one memory latency per 16 neighbours, sets the time of the whole kernel.  (Separate launches
+// for the segments and for the other rows were slower on every workload tried.)
 template <int P, int EPI>
 __global__ __launch_bounds__(kBlock) void bspmm_kernel(
     const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
     const int32_t *__restrict__ order, uint32_t N, const uint32_t *__restrict__ h32,
     int64_t h_stride32, int32_t C, int32_t W32, const uint32_t *__restrict__ seeds,
-    void *__restrict__ out, int64_t out_stride)
+    void *__restrict__ out, int64_t out_stride, RowSegments seg)
 {
     const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t slot = t / (uint32_t)W32;
-    const int w = (int)(t - slot * (uint32_t)W32);
-    const bool active = slot < N;
+    const uint64_t v = t / (uint32_t)W32; // virtual row
+    const int w = (int)(t - v * (uint32_t)W32);
+    const bool active = v < (uint64_t)seg.n_long_segs + (N - seg.n_long);
+    const bool part = v < seg.n_long_segs; // wave-uniform except at one boundary
+    uint32_t slot = 0, k = 0;
+    if (active) {
+        if (part) {
+            slot = seg.seg_slot[v];
+            k = (uint32_t)v - seg.seg_ptr[slot];
+        } else {
+            slot = seg.n_long + (uint32_t)(v - seg.n_long_segs);
+        }
+    }
     const uint32_t row = active ? (uint32_t)order[slot] : 0u;
-    uint32_t e = active ? rowptr[row] : 0u;
-    const uint32_t end = active ? rowptr[row + 1] : 0u;
-    const uint32_t deg = end - e;
+    const uint32_t rbeg = active ? rowptr[row] : 0u, rend = active ? rowptr[row + 1] : 0u;
+    uint32_t e = rbeg + k * seg.seg_len;
+    const uint32_t end = part && rend - e > seg.seg_len ? e + seg.seg_len : rend;
+    const uint32_t deg = rend - rbeg;
 
     uint32_t acc[P], pend[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((deg & 1u) * P + p) * W32 + w] : 0u;
+        // the threshold seed of a long row is added when its segments are
+        acc[p] = (EPI == BITGNN_EPI_THRESH_BITS && !part)
+                     ? seeds[((deg & 1u) * P + p) * W32 + w]
+                     : 0u;
         pend[p] = 0u;
     }
 
@@ -135,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
     // gathers are in flight together instead of one at a time, and the indices of the next
     // 16 neighbours are requested before this block's gathers are waited for, so that a long
     // row pays one memory latency per block instead of two
-    const uint32_t last = deg ? end - 1 : 0u;
+    const uint32_t last = end > e ? end - 1 : 0u;
     int32_t j[kGroup];
 #pragma unroll
     for (int u = 0; u < kGroup; ++u)
@@ -201,6 +232,46 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
 
     if (!active)
         return;
+    if (part) { // a segment counts at most seg_len: the planes above seg.planes are zero
+#pragma unroll
+        for (int p = 0; p < 12; ++p)
+            if (p < seg.planes)
+                seg.partial[((size_t)v * seg.planes + p) * W32 + w] = acc[p];
+        return;
+    }
+    bspmm_epilogue<P, EPI>(acc, deg, row, w, W32, C, out, out_stride);
+}
+
+// Long rows: the bit-sliced counts of a row's segments (and the threshold seed) are added
+// plane by plane with a carry, then the row is finished as any other.
+template <int P, int EPI>
+__global__ __launch_bounds__(kBlock) void bspmm_long_rows_kernel(
+    const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ order, int32_t C, int32_t W32,
+    const uint32_t *__restrict__ seeds, void *__restrict__ out, int64_t out_stride,
+    RowSegments seg)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t slot = t / (uint32_t)W32;
+    const int w = (int)(t - slot * (uint32_t)W32);
+    if (slot >= seg.n_long)
+        return;
+    const uint32_t row = (uint32_t)order[slot];
+    const uint32_t deg = rowptr[row + 1] - rowptr[row];
+    uint32_t acc[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((deg & 1u) * P + p) * W32 + w] : 0u;
+    for (uint32_t v = seg.seg_ptr[slot]; v < seg.seg_ptr[slot + 1]; ++v) {
+        uint32_t carry = 0;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t b =
+                p < seg.planes ? seg.partial[((size_t)v * seg.planes + p) * W32 + w] : 0u;
+            uint32_t nc;
+            csa(acc[p], b, carry, nc);
+            carry = nc;
+        }
+    }
     bspmm_epilogue<P, EPI>(acc, deg, row, w, W32, C, out, out_stride);
 }
 
@@ -248,16 +319,26 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
 template <int P>
 void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj *adj,
                     const int32_t *col, const uint32_t *h32, int64_t h_stride32, int32_t C,
-                    int32_t W32, const uint32_t *seeds, void *out, int64_t out_stride)
+                    int32_t W32, const uint32_t *seeds, void *out, int64_t out_stride,
+                    const RowSegments &seg)
 {
-    if (epilogue == BITGNN_EPI_THRESH_BITS)
+    const unsigned grid_long =
+        (unsigned)(((uint64_t)seg.n_long * (uint32_t)W32 + kBlock - 1) / kBlock);
+    if (epilogue == BITGNN_EPI_THRESH_BITS) {
         bspmm_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid, kBlock, 0, s>>>(
             adj->rowptr, col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds, out,
-            out_stride);
-    else
+            out_stride, seg);
+        if (grid_long)
+            bspmm_long_rows_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid_long, kBlock, 0, s>>>(
+                adj->rowptr, adj->order, C, W32, seeds, out, out_stride, seg);
+    } else {
         bspmm_kernel<P, BITGNN_EPI_RAW_I32><<<grid, kBlock, 0, s>>>(
             adj->rowptr, col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds, out,
-            out_stride);
+            out_stride, seg);
+        if (grid_long)
+            bspmm_long_rows_kernel<P, BITGNN_EPI_RAW_I32><<<grid_long, kBlock, 0, s>>>(
+                adj->rowptr, adj->order, C, W32, seeds, out, out_stride, seg);
+    }
 }
 
 // rows in degree order, W32 words each, no padding
@@ -1217,7 +1298,7 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
 // the blocked kernel by its id stream or, on small graphs, by the chain of LDS refills a
 // workgroup walks through, and it pays that once per 128-channel pass.
 bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
-                       double chain_us_per_nnz)
+                       double chain_us_per_nnz, int64_t longest_chain)
 {
     const bitgnn_blocked *b = adj->blk;
     if (!b)
@@ -1225,7 +1306,7 @@ bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
     if (b->forced)
         return true;
     const double csr_traffic = (double)adj->nnz * (double)bytes_per_nnz / 1.5e6;
-    const double csr_chain = (double)adj->max_degree * chain_us_per_nnz;
+    const double csr_chain = (double)longest_chain * chain_us_per_nnz;
     const double csr = (csr_traffic > csr_chain ? csr_traffic : csr_chain) + 10.0;
     const double stream = (double)b->n_groups * 64 * kGroupSteps / 1.3e6;
     const double rounds = (double)((b->n_wgs + 255) / 256);
@@ -1247,7 +1328,10 @@ static int launch_bspmm_path(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *a
     else if (adj->blk && !adj->blk->forced && adj->pref[passes < 4 ? passes - 1 : 3])
         blocked = adj->pref[passes < 4 ? passes - 1 : 3] == 2;
     else
-        blocked = bg_prefer_blocked(adj, passes, 4 * (int64_t)((C + 31) / 32), 0.06);
+        blocked = bg_prefer_blocked(adj, passes, 4 * (int64_t)((C + 31) / 32), 0.06,
+                                    adj->max_degree < (int64_t)adj->seg_len
+                                        ? adj->max_degree
+                                        : (int64_t)adj->seg_len);
     if (blocked)
         return bg_launch_bspmm_blocked(ctx, s, adj, hbits, C, h_stride, epilogue, T, out,
                                        out_stride);
@@ -1258,18 +1342,31 @@ static int launch_bspmm_path(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *a
     if (rc0 != BITGNN_OK)
         return rc0;
     const int64_t threads = adj->n * (int64_t)W32;
-    const int64_t grid = (threads + kBlock - 1) / kBlock;
-    BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm: N*C too large");
+    const int64_t pgrid = (threads + kBlock - 1) / kBlock;
+    // virtual rows: the segments of the long rows, then the other rows
+    const int64_t vrows = (int64_t)adj->n_long_segs + (adj->n - adj->n_long);
+    const int64_t grid = (vrows * W32 + kBlock - 1) / kBlock;
+    BG_REQUIRE(ctx, grid < (1ll << 31) && pgrid < (1ll << 31), BITGNN_ERR_UNSUPPORTED,
+               "bitgnn_bspmm: N*C too large");
     const uint32_t *h32 = (const uint32_t *)hbits;
     const int32_t *col = adj->col;
     int64_t hs32 = h_stride * 2;
-    if (adj->col_slot) { // gather from a degree-ordered copy of the rows
-        const int rc = bg_ws_reserve(ctx, (size_t)threads * 4);
+    const size_t perm_bytes = adj->col_slot ? (((size_t)threads * 4 + 255) & ~(size_t)255) : 0;
+    int seg_planes = 1;
+    while ((1u << seg_planes) <= adj->seg_len)
+        ++seg_planes;
+    const size_t seg_bytes = (size_t)adj->n_long_segs * seg_planes * W32 * 4;
+    if (perm_bytes + seg_bytes) {
+        const int rc = bg_ws_reserve(ctx, perm_bytes + seg_bytes);
         if (rc != BITGNN_OK)
             return rc;
-        csr_permute_kernel<<<(unsigned)grid, kBlock, 0, s>>>(h32, hs32, adj->order,
-                                                             (uint32_t)adj->n, W32,
-                                                             (uint32_t *)ctx->ws);
+    }
+    const RowSegments seg{adj->seg_ptr,  adj->seg_slot, adj->n_long, adj->n_long_segs,
+                          adj->seg_len,  seg_planes,    (uint32_t *)((char *)ctx->ws + perm_bytes)};
+    if (adj->col_slot) { // gather from a degree-ordered copy of the rows
+        csr_permute_kernel<<<(unsigned)pgrid, kBlock, 0, s>>>(h32, hs32, adj->order,
+                                                              (uint32_t)adj->n, W32,
+                                                              (uint32_t *)ctx->ws);
         BG_LAUNCH_CHECK(ctx, "csr_permute");
         h32 = (const uint32_t *)ctx->ws;
         hs32 = W32;
@@ -1279,19 +1376,19 @@ static int launch_bspmm_path(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *a
     switch (P) {
     case 12:
         launch_bspmm_p<12>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
-                           out_stride);
+                           out_stride, seg);
         break;
     case 16:
         launch_bspmm_p<16>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
-                           out_stride);
+                           out_stride, seg);
         break;
     case 20:
         launch_bspmm_p<20>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
-                           out_stride);
+                           out_stride, seg);
         break;
     default:
         launch_bspmm_p<26>(s, (unsigned)grid, epilogue, adj, col, h32, hs32, C, W32, seeds, out,
-                           out_stride);
+                           out_stride, seg);
         break;
     }
     bg_time_end(ctx, s);

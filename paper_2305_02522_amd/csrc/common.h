@@ -64,6 +64,11 @@ static_assert(kGroupSteps == 8 || kGroupSteps == 16, "groups of 8 or 16 steps");
 // where that is what it takes to give every compute unit a work item.
 static const int kSlicesPerWg = 16;
 
+// Segment lengths of the CSR bit-SpMM (see bitgnn_adj::seg_len) and the non-zero count from
+// which the long one is used.
+static const uint32_t kSegLenSmall = 128, kSegLenLarge = 1024;
+static const int64_t kSegLargeNnz = 1ll << 24;
+
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
@@ -98,6 +103,15 @@ struct bitgnn_adj {
     int32_t *order;   // [n] rows by decreasing degree
     int32_t *col_slot; // [nnz] column indices as degree-order slots (large CSR-only graphs:
                        // gathers from a degree-ordered copy keep the hubs' rows together)
+    // Row segments of the CSR bit-SpMM: a row longer than seg_len neighbours is walked by
+    // several thread groups, seg_len neighbours each (such rows come first in `order`).
+    uint32_t seg_len;   // 128 on small graphs, where the longest row's serial walk is what
+                        // the kernel waits for; 1024 on large ones, where only true hubs are
+                        // worth the segments' extra pass (a power of two, at most 1024)
+    uint32_t *seg_ptr;  // [n_long + 1] by degree-order slot: first segment of the long row
+    uint32_t *seg_slot; // [n_long_segs] segment -> degree-order slot of its row
+    uint32_t n_long;      // rows with more than seg_len neighbours
+    uint32_t n_long_segs; // their segments
     size_t device_bytes;
     bitgnn_blocked *blk; // null when the graph is too sparse for the blocked path
     // bitgnn_adj_tune's verdict for bit aggregations of 1, 2, 3, >= 4 passes of 128 channels:
@@ -176,8 +190,9 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
 int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes);
 // Whether the blocked form is expected to beat the CSR kernel for rows of `bytes_per_nnz`
 // gathered bytes per non-zero, handled in `passes` passes of the blocked kernel.
+// `longest_chain`: neighbours the CSR kernel in question walks serially at most.
 bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
-                       double chain_us_per_nnz);
+                       double chain_us_per_nnz, int64_t longest_chain);
 int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
                                   const uint64_t *hbits, int32_t K, int64_t h_stride,
                                   const uint64_t *wbits, int32_t M, int64_t w_stride,
