@@ -277,20 +277,32 @@ __global__ __launch_bounds__(kBlock) void bspmm_long_rows_kernel(
 
 // Integer aggregation of the last GCN layer: a group of LPR lanes owns a node,
 // lane li sums channel li of the neighbours' int32 rows (coalesced row reads).
+// Rows longer than a segment are split as in bspmm_kernel: a segment leaves its int32 sums
+// in seg.partial ([segment][M]) and spmm_i32_long_rows_kernel adds a row's segments.
 template <bool SCALE>
 __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
     const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
     const int32_t *__restrict__ order, uint32_t N, const int32_t *__restrict__ Z, int32_t M,
     int64_t z_stride, const float *__restrict__ alpha, void *__restrict__ out,
-    int64_t out_stride, int lpr_log2)
+    int64_t out_stride, int lpr_log2, RowSegments seg)
 {
     const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t slot = t >> lpr_log2;
+    const uint64_t v = t >> lpr_log2; // virtual row: a segment of a long row, or a whole row
     const int li = (int)(t & ((1u << lpr_log2) - 1u));
-    if (slot >= N)
+    if (v >= (uint64_t)seg.n_long_segs + (N - seg.n_long))
         return;
+    const bool part = v < seg.n_long_segs;
+    uint32_t slot, k = 0;
+    if (part) {
+        slot = seg.seg_slot[v];
+        k = (uint32_t)v - seg.seg_ptr[slot];
+    } else {
+        slot = seg.n_long + (uint32_t)(v - seg.n_long_segs);
+    }
     const uint32_t row = (uint32_t)order[slot];
-    const uint32_t beg = rowptr[row], end = rowptr[row + 1];
+    const uint32_t rend = rowptr[row + 1];
+    const uint32_t beg = rowptr[row] + k * seg.seg_len;
+    const uint32_t end = part && rend - beg > seg.seg_len ? beg + seg.seg_len : rend;
     for (int c = li; c < M; c += (1 << lpr_log2)) {
         int32_t sum = 0;
         // eight neighbours per turn: their indices, then their values, are in flight
@@ -307,6 +319,30 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
             for (int u = 0; u < 8; ++u)
                 sum += e + u < end ? z[u] : 0;
         }
+        if (part)
+            ((int32_t *)seg.partial)[(size_t)v * M + c] = sum;
+        else if (SCALE)
+            ((float *)out)[(int64_t)row * out_stride + c] = alpha[c] * (float)sum;
+        else
+            ((int32_t *)out)[(int64_t)row * out_stride + c] = sum;
+    }
+}
+
+template <bool SCALE>
+__global__ __launch_bounds__(kBlock) void spmm_i32_long_rows_kernel(
+    const int32_t *__restrict__ order, int32_t M, const float *__restrict__ alpha,
+    void *__restrict__ out, int64_t out_stride, int lpr_log2, RowSegments seg)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t slot = t >> lpr_log2;
+    const int li = (int)(t & ((1u << lpr_log2) - 1u));
+    if (slot >= seg.n_long)
+        return;
+    const uint32_t row = (uint32_t)order[slot];
+    for (int c = li; c < M; c += (1 << lpr_log2)) {
+        int32_t sum = 0;
+        for (uint32_t v = seg.seg_ptr[slot]; v < seg.seg_ptr[slot + 1]; ++v)
+            sum += ((const int32_t *)seg.partial)[(size_t)v * M + c];
         if (SCALE)
             ((float *)out)[(int64_t)row * out_stride + c] = alpha[c] * (float)sum;
         else
@@ -1305,7 +1341,9 @@ bool bg_prefer_blocked(const bitgnn_adj *adj, int passes, int64_t bytes_per_nnz,
         return false;
     if (b->forced)
         return true;
-    const double csr_traffic = (double)adj->nnz * (double)bytes_per_nnz / 1.5e6;
+    // a gathered row costs its cache line plus its bytes: ~11 us per million 32-byte rows
+    // (config 5), ~27 us per million 160-byte rows (the integer rows of an output layer)
+    const double csr_traffic = (double)adj->nnz * (8.0 + 0.12 * (double)bytes_per_nnz) / 1e6;
     const double csr_chain = (double)longest_chain * chain_us_per_nnz;
     const double csr = (csr_traffic > csr_chain ? csr_traffic : csr_chain) + 10.0;
     const double stream = (double)b->n_groups * 64 * kGroupSteps / 1.3e6;
@@ -1520,17 +1558,32 @@ int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, co
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < M && lpr_log2 < 6)
         ++lpr_log2;
-    const int64_t threads = adj->n << lpr_log2;
-    const int64_t grid = (threads + kBlock - 1) / kBlock;
+    const int64_t vrows = (int64_t)adj->n_long_segs + (adj->n - adj->n_long);
+    const int64_t grid = ((vrows << lpr_log2) + kBlock - 1) / kBlock;
     BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_spmm_i32: N too large");
+    if (adj->n_long_segs) {
+        const int rc = bg_ws_reserve(ctx, (size_t)adj->n_long_segs * M * 4);
+        if (rc != BITGNN_OK)
+            return rc;
+    }
+    const RowSegments seg{adj->seg_ptr, adj->seg_slot, adj->n_long, adj->n_long_segs,
+                          adj->seg_len, 0,             (uint32_t *)ctx->ws};
+    const unsigned grid_long =
+        (unsigned)((((uint64_t)adj->n_long << lpr_log2) + kBlock - 1) / kBlock);
+#define BG_SPMM_I32(SV)                                                                           \
+    do {                                                                                          \
+        spmm_i32_kernel<SV><<<(unsigned)grid, kBlock, 0, s>>>(                                    \
+            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,      \
+            out_stride, lpr_log2, seg);                                                           \
+        if (grid_long)                                                                            \
+            spmm_i32_long_rows_kernel<SV><<<grid_long, kBlock, 0, s>>>(                           \
+                adj->order, M, alpha, out, out_stride, lpr_log2, seg);                            \
+    } while (0)
     if (alpha)
-        spmm_i32_kernel<true><<<(unsigned)grid, kBlock, 0, s>>>(
-            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,
-            out_stride, lpr_log2);
+        BG_SPMM_I32(true);
     else
-        spmm_i32_kernel<false><<<(unsigned)grid, kBlock, 0, s>>>(
-            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,
-            out_stride, lpr_log2);
+        BG_SPMM_I32(false);
+#undef BG_SPMM_I32
     BG_LAUNCH_CHECK(ctx, "bitgnn_spmm_i32");
     return BITGNN_OK;
 }

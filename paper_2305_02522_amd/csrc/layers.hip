@@ -90,7 +90,9 @@ extern "C" int bitgnn_gcn_out_layer(bitgnn_ctx *ctx, void *stream, const bitgnn_
     // merge step (tmp_i32 chains the integer sums of the passes when K > 128); otherwise
     // the int32 rows of x W are aggregated directly.
     if ((int64_t)K * adj->max_degree < (1ll << 29) &&
-        bg_prefer_blocked(adj, (K + 127) / 128, 4 * (int64_t)M, 0.25, adj->max_degree))
+        bg_prefer_blocked(adj, (K + 127) / 128, 4 * (int64_t)M, 0.25,
+                          adj->max_degree < (int64_t)adj->seg_len ? adj->max_degree
+                                                                  : (int64_t)adj->seg_len))
         return bg_launch_agg_project_blocked(ctx, s, adj, xbits, K, x_stride, wbits, M, w_stride,
                                              alpha, tmp_i32, logits, ldo);
     rc = bg_launch_bgemm(ctx, s, xbits, n, x_stride, K, kwords, wbits, M, w_stride,
