@@ -379,6 +379,11 @@ def main():
         elif lab.endswith(".out_layer") and blocked["parts"] and wl.dims[-2] <= 128:
             agg_labels.append(lab)
     agg_kernel_ms = {}
+    csr_labels = [l for l in labels if l and l.endswith(".bspmm")]
+    took_blocked = bool(blocked["parts"]) and bool(agg_labels) and \
+        len(agg_ms) == len(agg_labels) * args.steps
+    if not took_blocked and csr_labels and len(agg_ms) == len(csr_labels) * args.steps:
+        agg_labels = csr_labels          # the library chose the CSR kernel: one launch per call
     if agg_labels and len(agg_ms) == len(agg_labels) * args.steps:
         for i, lab in enumerate(agg_labels):
             agg_kernel_ms.setdefault(lab, []).extend(agg_ms[i::len(agg_labels)])
@@ -408,7 +413,7 @@ def main():
     dom = max(per_op, key=lambda lab: kernel_time_ms(lab)[0] * kernel_time_ms(lab)[1])
     dm = models[dom]
     davg, launches = kernel_time_ms(dom)
-    kname = {"bspmm": "bspmm_blk_kernel" if blocked["parts"] else "bspmm_kernel",
+    kname = {"bspmm": "bspmm_blk_kernel" if took_blocked else "bspmm_kernel",
              "out_layer": "bspmm_blk_kernel" if dom in agg_kernel_ms else "spmm_i32_kernel",
              "bgemm_f32": "bgemm_f32_kernel", "bgemm": "bgemm_kernel",
              "gcn2_fused": "gcn2_fused_kernel",

@@ -243,7 +243,24 @@ __global__ __launch_bounds__(kBlock) void bspmm_kernel(
 }
 
 // Long rows: the bit-sliced counts of a row's segments (and the threshold seed) are added
-// plane by plane with a carry, then the row is finished as any other.
+// plane by plane with a carry, then the row is finished as any other.  kMergeLanes lanes
+// share a (row, word): each adds every kMergeLanes-th segment (a hub has a hundred and more,
+// and one lane would pay a memory latency for each), then the lanes' sums are added pairwise
+// across the lanes.
+constexpr int kMergeLanes = 16;
+
+template <int P>
+__device__ __forceinline__ void planes_add(uint32_t (&acc)[P], const uint32_t (&b)[P])
+{
+    uint32_t carry = 0;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        uint32_t nc;
+        csa(acc[p], b[p], carry, nc);
+        carry = nc;
+    }
+}
+
 template <int P, int EPI>
 __global__ __launch_bounds__(kBlock) void bspmm_long_rows_kernel(
     const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ order, int32_t C, int32_t W32,
@@ -251,32 +268,48 @@ __global__ __launch_bounds__(kBlock) void bspmm_long_rows_kernel(
     RowSegments seg)
 {
     const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t slot = t / (uint32_t)W32;
-    const int w = (int)(t - slot * (uint32_t)W32);
-    if (slot >= seg.n_long)
-        return;
-    const uint32_t row = (uint32_t)order[slot];
-    const uint32_t deg = rowptr[row + 1] - rowptr[row];
+    const int q = (int)(t % kMergeLanes);
+    const uint64_t g = t / kMergeLanes; // (row, word); its lanes sit side by side in a wavefront
+    const uint64_t slot = g / (uint32_t)W32;
+    const int w = (int)(g - slot * (uint32_t)W32);
+    const bool active = slot < seg.n_long; // the same for the kMergeLanes lanes of a group
     uint32_t acc[P];
 #pragma unroll
     for (int p = 0; p < P; ++p)
-        acc[p] = (EPI == BITGNN_EPI_THRESH_BITS) ? seeds[((deg & 1u) * P + p) * W32 + w] : 0u;
-    for (uint32_t v = seg.seg_ptr[slot]; v < seg.seg_ptr[slot + 1]; ++v) {
-        uint32_t carry = 0;
+        acc[p] = 0u;
+    if (active) {
+        const uint32_t vend = seg.seg_ptr[slot + 1];
+        for (uint32_t v = seg.seg_ptr[slot] + (uint32_t)q; v < vend; v += kMergeLanes) {
+            uint32_t b[P];
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const uint32_t b =
-                p < seg.planes ? seg.partial[((size_t)v * seg.planes + p) * W32 + w] : 0u;
-            uint32_t nc;
-            csa(acc[p], b, carry, nc);
-            carry = nc;
+            for (int p = 0; p < P; ++p)
+                b[p] = p < seg.planes ? seg.partial[((size_t)v * seg.planes + p) * W32 + w] : 0u;
+            planes_add<P>(acc, b);
         }
+    }
+    // all lanes of the wavefront take part in the exchanges
+#pragma unroll
+    for (int d = kMergeLanes / 2; d >= 1; d >>= 1) {
+        uint32_t b[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            b[p] = (uint32_t)__shfl_xor((int)acc[p], d);
+        planes_add<P>(acc, b);
+    }
+    if (!active || q != 0)
+        return;
+    const uint32_t row = (uint32_t)order[slot];
+    const uint32_t deg = rowptr[row + 1] - rowptr[row];
+    if (EPI == BITGNN_EPI_THRESH_BITS) {
+        uint32_t sd[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            sd[p] = seeds[((deg & 1u) * P + p) * W32 + w];
+        planes_add<P>(acc, sd);
     }
     bspmm_epilogue<P, EPI>(acc, deg, row, w, W32, C, out, out_stride);
 }
 
-// Integer aggregation of the last GCN layer: a group of LPR lanes owns a node,
-// lane li sums channel li of the neighbours' int32 rows (coalesced row reads).
 // Rows longer than a segment are split as in bspmm_kernel: a segment leaves its int32 sums
 // in seg.partial ([segment][M]) and spmm_i32_long_rows_kernel adds a row's segments.
 template <bool SCALE>
@@ -341,8 +374,16 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_long_rows_kernel(
     const uint32_t row = (uint32_t)order[slot];
     for (int c = li; c < M; c += (1 << lpr_log2)) {
         int32_t sum = 0;
-        for (uint32_t v = seg.seg_ptr[slot]; v < seg.seg_ptr[slot + 1]; ++v)
-            sum += ((const int32_t *)seg.partial)[(size_t)v * M + c];
+        const uint32_t vend = seg.seg_ptr[slot + 1];
+        for (uint32_t v0 = seg.seg_ptr[slot]; v0 < vend; v0 += 8) { // eight loads in flight
+            int32_t z[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                z[q] = v0 + q < vend ? ((const int32_t *)seg.partial)[(size_t)(v0 + q) * M + c] : 0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                sum += z[q];
+        }
         if (SCALE)
             ((float *)out)[(int64_t)row * out_stride + c] = alpha[c] * (float)sum;
         else
@@ -359,7 +400,7 @@ void launch_bspmm_p(hipStream_t s, unsigned grid, int epilogue, const bitgnn_adj
                     const RowSegments &seg)
 {
     const unsigned grid_long =
-        (unsigned)(((uint64_t)seg.n_long * (uint32_t)W32 + kBlock - 1) / kBlock);
+        (unsigned)(((uint64_t)seg.n_long * (uint32_t)W32 * kMergeLanes + kBlock - 1) / kBlock);
     if (epilogue == BITGNN_EPI_THRESH_BITS) {
         bspmm_kernel<P, BITGNN_EPI_THRESH_BITS><<<grid, kBlock, 0, s>>>(
             adj->rowptr, col, adj->order, (uint32_t)adj->n, h32, h_stride32, C, W32, seeds, out,
