@@ -361,6 +361,82 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_kernel(
     }
 }
 
+// The same aggregation for wide rows (more than 32 channels) whose int32 rows can be read
+// VW values per lane (16 or 8 bytes): one wavefront per virtual row, LR = M / VW lanes cover
+// a neighbour's row, so one gather instruction fetches 64 / LR neighbours instead of one --
+// the chip issues ~35 G wavefront-wide gathers per second whatever they carry, and a lane
+// per channel spends one per neighbour.  The neighbour slots' sums are added across the
+// lanes at the end (integer sums do not depend on the order).
+template <bool SCALE, int VW>
+__global__ __launch_bounds__(kBlock) void spmm_i32_wide_kernel(
+    const uint32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
+    const int32_t *__restrict__ order, uint32_t N, const int32_t *__restrict__ Z, int32_t M,
+    int64_t z_stride, const float *__restrict__ alpha, void *__restrict__ out,
+    int64_t out_stride, RowSegments seg)
+{
+    typedef int32_t vec_t __attribute__((ext_vector_type(VW)));
+    const int lane = threadIdx.x & 63;
+    const uint64_t v = (uint64_t)blockIdx.x * (kBlock / 64) +
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (v >= (uint64_t)seg.n_long_segs + (N - seg.n_long)) // wave-uniform
+        return;
+    const bool part = v < seg.n_long_segs;
+    uint32_t slot, k = 0;
+    if (part) {
+        slot = seg.seg_slot[v];
+        k = (uint32_t)v - seg.seg_ptr[slot];
+    } else {
+        slot = seg.n_long + (uint32_t)(v - seg.n_long_segs);
+    }
+    const uint32_t row = (uint32_t)order[slot];
+    const uint32_t rend = rowptr[row + 1];
+    const uint32_t beg = rowptr[row] + k * seg.seg_len;
+    const uint32_t end = part && rend - beg > seg.seg_len ? beg + seg.seg_len : rend;
+    const int LR = M / VW;  // lanes per neighbour row
+    const int Q = 64 / LR;  // neighbour slots of the wavefront
+    const int q = lane / LR, r = lane - q * LR;
+    const bool has_slot = q < Q;
+    vec_t acc = 0;
+    for (uint32_t e0 = beg; e0 < end; e0 += 64) {
+        const int cnt = end - e0 < 64u ? (int)(end - e0) : 64;
+        const int32_t jl = col[e0 + (uint32_t)(lane < cnt ? lane : cnt - 1)];
+        for (int t0 = 0; t0 < cnt; t0 += 4 * Q) {
+            vec_t z[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { // clamped loads, masked below
+                const int t = t0 + u * Q + q;
+                const int32_t j = __shfl(jl, t < cnt ? t : cnt - 1, 64);
+                z[u] = *(const vec_t *)(Z + (int64_t)j * z_stride + r * VW);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (has_slot && t0 + u * Q + q < cnt)
+                    acc += z[u];
+        }
+    }
+    // lanes of slot 0 collect the other slots' sums
+    for (int kq = 1; kq < Q; ++kq) {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) {
+            const int32_t other = __shfl(acc[i], lane + kq * LR, 64);
+            if (q == 0)
+                acc[i] += other;
+        }
+    }
+    if (q != 0)
+        return;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) {
+        const int c = r * VW + i;
+        if (part)
+            ((int32_t *)seg.partial)[(size_t)v * M + c] = acc[i];
+        else if (SCALE)
+            ((float *)out)[(int64_t)row * out_stride + c] = alpha[c] * (float)acc[i];
+        else
+            ((int32_t *)out)[(int64_t)row * out_stride + c] = acc[i];
+    }
+}
+
 template <bool SCALE>
 __global__ __launch_bounds__(kBlock) void spmm_i32_long_rows_kernel(
     const int32_t *__restrict__ order, int32_t M, const float *__restrict__ alpha,
@@ -1611,11 +1687,26 @@ int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, co
                           adj->seg_len, 0,             (uint32_t *)ctx->ws};
     const unsigned grid_long =
         (unsigned)((((uint64_t)adj->n_long << lpr_log2) + kBlock - 1) / kBlock);
+    // wide rows that can be read 4 or 2 values per lane: several neighbours per gather
+    const int vw = (M > 32 && M % 4 == 0 && z_stride % 4 == 0 && bg_aligned(Z, 16) && M <= 128) ? 4
+                   : (M > 32 && M % 2 == 0 && z_stride % 2 == 0 && bg_aligned(Z, 8) && M <= 64)
+                       ? 2
+                       : 1;
+    const unsigned grid_wide = (unsigned)((vrows + kBlock / 64 - 1) / (kBlock / 64));
 #define BG_SPMM_I32(SV)                                                                           \
     do {                                                                                          \
-        spmm_i32_kernel<SV><<<(unsigned)grid, kBlock, 0, s>>>(                                    \
-            adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,      \
-            out_stride, lpr_log2, seg);                                                           \
+        if (vw == 4)                                                                              \
+            spmm_i32_wide_kernel<SV, 4><<<grid_wide, kBlock, 0, s>>>(                             \
+                adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,  \
+                out_stride, seg);                                                                 \
+        else if (vw == 2)                                                                         \
+            spmm_i32_wide_kernel<SV, 2><<<grid_wide, kBlock, 0, s>>>(                             \
+                adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,  \
+                out_stride, seg);                                                                 \
+        else                                                                                      \
+            spmm_i32_kernel<SV><<<(unsigned)grid, kBlock, 0, s>>>(                                \
+                adj->rowptr, adj->col, adj->order, (uint32_t)adj->n, Z, M, z_stride, alpha, out,  \
+                out_stride, lpr_log2, seg);                                                       \
         if (grid_long)                                                                            \
             spmm_i32_long_rows_kernel<SV><<<grid_long, kBlock, 0, s>>>(                           \
                 adj->order, M, alpha, out, out_stride, lpr_log2, seg);                            \

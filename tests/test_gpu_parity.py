@@ -381,10 +381,15 @@ def test_gcn_layer_tune_measures_both_recipes(B, ctx):
     adj.close()
 
 
-@pytest.mark.parametrize("n,e,M", [(50, 200, 1), (1000, 9000, 7), (3000, 50000, 41),
-                                   (500, 4000, 64), (300, 2000, 130)])
-def test_spmm_i32(B, ctx, n, e, M):
-    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + M)
+@pytest.mark.parametrize("n,e,M,hubs", [
+    (50, 200, 1, 0), (1000, 9000, 7, 0), (3000, 50000, 41, 0), (500, 4000, 64, 0),
+    (300, 2000, 130, 0),
+    (3000, 30000, 40, 1),      # 16-byte reads, 6 neighbours per gather, rows longer than a segment
+    (2000, 20000, 128, 1),     # 16-byte reads, 2 neighbours per gather
+    (2500, 30000, 34, 0),      # 8-byte reads
+    (4000, 20000, 7, 2)])      # narrow rows with split rows
+def test_spmm_i32(B, ctx, n, e, M, hubs):
+    adj, rp, col, r = _graph(B, ctx, n, e, SYM_LOOPS, n + M, hubs)
     z = r.integers(-600, 601, size=(n, M)).astype(np.int32)
     y = orc.spmm_i64(rp, col, z)
     out = torch.zeros((n, M), dtype=torch.int32, device="cuda")
