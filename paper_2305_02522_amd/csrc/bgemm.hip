@@ -115,7 +115,9 @@ constexpr int kRowsF = 16;
 template <int TILES>
 struct f32_chunk {
     // 32-bit weight words per K chunk held in registers (two per vote of 64 floats)
+    // (four tiles: 16 words where the last chunk of a row would be mostly full, else 8)
     static constexpr int words = TILES <= 2 ? 20 : 8;
+    static constexpr int words_long = TILES <= 2 ? 20 : 16;
 };
 
 template <int VOTES, bool HAS_TAU>
@@ -174,14 +176,13 @@ __device__ __forceinline__ void f32_finish_row(int r, int64_t row, bool row_ok, 
 
 // SINGLE: all of K fits one register chunk, so a row is finished as soon as it has been
 // read and no per-row accumulators are kept.
-template <int EPI, int TILES, bool HAS_TAU, bool SINGLE>
+template <int EPI, int TILES, bool HAS_TAU, bool SINGLE, int kWords = f32_chunk<TILES>::words>
 __global__ __launch_bounds__(kWaves * 64) void bgemm_f32_kernel(
     const float *__restrict__ x, int64_t n, int32_t K, int64_t ldx, const float *__restrict__ tau,
     int32_t kw32, const uint32_t *__restrict__ w32, int32_t M, int64_t w_stride32,
     const int32_t *__restrict__ T, const float *__restrict__ alpha, void *__restrict__ out,
     int64_t out_stride)
 {
-    constexpr int kWords = f32_chunk<TILES>::words;
     constexpr int kVotes = kWords / 2;
     constexpr int kAccRows = SINGLE ? 2 : kRowsF;
     const int lane = threadIdx.x & 63;
@@ -275,10 +276,19 @@ void launch_bgemm_f32(hipStream_t s, dim3 grid, const float *x, int64_t n, int32
                       int64_t w_stride32, const int32_t *T, const float *alpha, void *out,
                       int64_t out_stride)
 {
+    // chunk of the K axis: the long one if its last step over a row wastes under 8 words
+    constexpr int kLong = f32_chunk<TILES>::words_long, kShort = f32_chunk<TILES>::words;
+    const bool use_long = kLong != kShort && ((kw32 + kLong - 1) / kLong) * kLong - kw32 < 8;
 #define BG_F32(TAU, SINGLE)                                                                       \
-    bgemm_f32_kernel<EPI, TILES, TAU, SINGLE><<<grid, kWaves * 64, 0, s>>>(                       \
-        x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride)
-    const bool single = kw32 <= f32_chunk<TILES>::words;
+    do {                                                                                          \
+        if (use_long)                                                                             \
+            bgemm_f32_kernel<EPI, TILES, TAU, SINGLE, kLong><<<grid, kWaves * 64, 0, s>>>(        \
+                x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);          \
+        else                                                                                      \
+            bgemm_f32_kernel<EPI, TILES, TAU, SINGLE, kShort><<<grid, kWaves * 64, 0, s>>>(       \
+                x, n, K, ldx, tau, kw32, w32, M, w_stride32, T, alpha, out, out_stride);          \
+    } while (0)
+    const bool single = kw32 <= (use_long ? kLong : kShort);
     if (tau) {
         if (single)
             BG_F32(true, true);
