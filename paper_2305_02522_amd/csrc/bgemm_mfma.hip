@@ -255,8 +255,10 @@ bool bg_bgemm_mfma_applies(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int
     if (ctx->bgemm_path == 2)
         return true;
     // measured on MI355X: the fixed cost (widening the weights, one LDS copy of them per
-    // workgroup) is repaid from about 10^5 rows on; 1.4x - 2.4x faster beyond
-    return n >= 100000;
+    // workgroup: 11-22 us whatever n) is repaid from 40-70 thousand rows on, depending on
+    // the shape (K x M = 512 x 256: level at 70 K; 128 x 128: from 20 K; 256 x 40: only
+    // beyond 100 K); 1.4x - 2.4x faster for large n
+    return n >= 65536;
 }
 
 int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
