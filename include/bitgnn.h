@@ -12,16 +12,20 @@
  *    A message for the last failure of a context is kept in the context
  *    (bitgnn_last_error).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Compute calls only enqueue work on it and return; bitgnn_adj_build
- *    synchronizes the stream before it returns.  A context serves ONE stream at
- *    a time: it owns a small device scratch table that concurrent calls would
- *    race on.
+ *    Compute calls only enqueue work on it and return: they never allocate,
+ *    free or synchronize, so they may be recorded into a HIP graph.  The set-up
+ *    calls (bitgnn_ctx_create, bitgnn_ctx_reserve, bitgnn_adj_build and the
+ *    *_tune utilities) allocate and synchronize.  A context serves ONE stream at
+ *    a time: it owns device scratch that concurrent calls would race on.
  *  - every data pointer is a DEVICE pointer owned by the caller and must stay
  *    valid until the enqueued work has run.  The library allocates device
- *    memory only inside a bitgnn_adj and inside a context (a few KB, plus a
- *    grow-only workspace for the blocked aggregation: 16 B per node and 160 B
- *    per row part; it grows, with a device synchronization, the first time a
- *    larger graph is aggregated, never afterwards).
+ *    memory only inside a bitgnn_adj and inside a context: a few hundred KB of
+ *    fixed scratch, plus the aggregation workspace (degree-ordered activation
+ *    rows, partial counters of row parts and segments).  bitgnn_adj_build
+ *    reserves that workspace for aggregations of up to
+ *    BITGNN_DEFAULT_WS_CHANNELS channels and BITGNN_DEFAULT_WS_CLASSES classes
+ *    on the graph it builds; wider calls need bitgnn_adj_workspace_bytes +
+ *    bitgnn_ctx_reserve first and fail with BITGNN_ERR_WORKSPACE otherwise.
  *  - packed bit layout (part of the ABI): a packed matrix is row-major
  *    uint64 words, little endian; logical bit k of a row is bit (k % 64) of
  *    word (k / 64); bit 1 encodes +1 and bit 0 encodes -1.  Rows are addressed
@@ -54,7 +58,19 @@ enum {
     BITGNN_ERR_RANGE = -4,       /* an int32 accumulator or a 32-bit offset could overflow */
     BITGNN_ERR_HIP = -5,         /* a HIP runtime call failed (code in the message) */
     BITGNN_ERR_UNSUPPORTED = -6, /* size beyond what the kernels are built for */
-    BITGNN_ERR_NO_DEVICE = -7    /* arguments are valid but the context has no GPU */
+    BITGNN_ERR_NO_DEVICE = -7,   /* arguments are valid but the context has no GPU */
+    BITGNN_ERR_WORKSPACE = -8    /* the context workspace is too small for this call:
+                                    bitgnn_adj_workspace_bytes + bitgnn_ctx_reserve */
+};
+
+/* Widths for which bitgnn_adj_build reserves the context workspace by itself. */
+#define BITGNN_DEFAULT_WS_CHANNELS 256
+#define BITGNN_DEFAULT_WS_CLASSES 64
+
+enum { /* kernels of the BMM (Section 2.2), bitgnn_ctx_set_bgemm_path */
+    BITGNN_BGEMM_AUTO = 0, /* chosen per shape from measured crossovers */
+    BITGNN_BGEMM_VALU = 1, /* xor + popcount on the vector ALUs */
+    BITGNN_BGEMM_MFMA = 2  /* bits widened to bytes, int8 matrix cores */
 };
 
 enum {
@@ -89,6 +105,23 @@ const char *bitgnn_last_error(const bitgnn_ctx *ctx);
  * not depend on these values.  Defaults: 8192, 255, 8. */
 int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
                           int32_t min_avg_degree);
+
+/* Forces one of the two BMM kernels (tests, A/B measurements); BITGNN_BGEMM_MFMA still
+ * falls back to the VALU kernel for shapes whose weights do not fit the matrix-core
+ * kernel's LDS.  Results never depend on the choice.  Default: BITGNN_BGEMM_AUTO. */
+int bitgnn_ctx_set_bgemm_path(bitgnn_ctx *ctx, int path);
+/* Which kernel bitgnn_bgemm launches for n rows of kwords 64-bit words against M weight
+ * rows under the context's current setting: *kernel <- BITGNN_BGEMM_VALU or _MFMA.  Host
+ * only; works on any context. */
+int bitgnn_ctx_bgemm_kernel(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int32_t M,
+                            int *kernel);
+
+/* Grows the context's aggregation workspace to at least `bytes` (never shrinks it).  A
+ * set-up call: it allocates, and synchronizes the device when it replaces a smaller
+ * workspace, so no work of this context may be in flight or being captured.
+ * bitgnn_ctx_workspace reports the current size. */
+int bitgnn_ctx_reserve(bitgnn_ctx *ctx, size_t bytes);
+int bitgnn_ctx_workspace(const bitgnn_ctx *ctx, size_t *bytes);
 
 /* Optional timing of the main aggregation kernel of every bit-SpMM call (the
  * LDS-staged kernel, or the CSR kernel on sparse graphs; the small permute / merge
@@ -126,10 +159,17 @@ int bitgnn_pack_weights_i8(bitgnn_ctx *ctx, void *stream, const int8_t *w, int32
  * src, dst: int32 [E] device arrays, left unchanged.  Requires
  * E*(1 + symmetrize) + N < 2^31.  Synchronizes `stream`.  Temporary sort
  * buffers are freed before returning; the handle keeps the CSR arrays, the
- * degrees and a degree-sorted row order.
+ * degrees and a degree-sorted row order.  Also grows the context's aggregation
+ * workspace (bitgnn_ctx_reserve) to what this graph needs at the default widths.
  * Errors: BITGNN_ERR_INDEX_RANGE if an endpoint is outside [0, N). */
 int bitgnn_adj_build(bitgnn_ctx *ctx, void *stream, const int32_t *src, const int32_t *dst,
                      int64_t E, int64_t N, uint32_t flags, bitgnn_adj **out);
+/* Context workspace (bytes) that compute calls on `adj` use at most when they aggregate
+ * up to C_max channels (bit or float rows; 1..2048) and produce up to M_max classes
+ * (bitgnn_spmm_i32, output layers).  Pass the result to bitgnn_ctx_reserve before the
+ * first such call when C_max or M_max exceed the defaults bitgnn_adj_build reserves for. */
+int bitgnn_adj_workspace_bytes(const bitgnn_adj *adj, int32_t C_max, int32_t M_max,
+                               size_t *bytes);
 /* Any output pointer may be NULL. */
 int bitgnn_adj_info(const bitgnn_adj *adj, int64_t *N, int64_t *nnz, int64_t *max_degree,
                     size_t *device_bytes);

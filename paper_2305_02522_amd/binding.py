@@ -22,6 +22,9 @@ ERR_RANGE = -4
 ERR_HIP = -5
 ERR_UNSUPPORTED = -6
 ERR_NO_DEVICE = -7
+ERR_WORKSPACE = -8
+
+BGEMM_AUTO, BGEMM_VALU, BGEMM_MFMA = 0, 1, 2
 
 ADJ_SYMMETRIZE = 1
 ADJ_ADD_SELF_LOOPS = 2
@@ -45,6 +48,11 @@ _SIGNATURES = {
     "bitgnn_ctx_destroy": (None, [_vp]),
     "bitgnn_last_error": (ctypes.c_char_p, [_vp]),
     "bitgnn_ctx_set_tuning": (_int, [_vp, _i32, _i32, _i32]),
+    "bitgnn_ctx_set_bgemm_path": (_int, [_vp, _int]),
+    "bitgnn_ctx_bgemm_kernel": (_int, [_vp, _i64, _i32, _i32, ctypes.POINTER(_int)]),
+    "bitgnn_ctx_reserve": (_int, [_vp, ctypes.c_size_t]),
+    "bitgnn_ctx_workspace": (_int, [_vp, ctypes.POINTER(ctypes.c_size_t)]),
+    "bitgnn_adj_workspace_bytes": (_int, [_vp, _i32, _i32, ctypes.POINTER(ctypes.c_size_t)]),
     "bitgnn_ctx_kernel_timing": (_int, [_vp, _int]),
     "bitgnn_ctx_kernel_times": (_int, [_vp, ctypes.POINTER(ctypes.c_float), _i32,
                                        ctypes.POINTER(_i32)]),
@@ -196,6 +204,34 @@ def words(k: int) -> int:
 
 def ctx_set_tuning(ctx: Context, cb_nodes: int, part_len: int, min_avg_degree: int):
     ctx.check(_lib.bitgnn_ctx_set_tuning(ctx.handle, cb_nodes, part_len, min_avg_degree))
+
+
+def ctx_set_bgemm_path(ctx: Context, path: int):
+    ctx.check(_lib.bitgnn_ctx_set_bgemm_path(ctx.handle, path))
+
+
+def ctx_bgemm_kernel(ctx: Context, n: int, kwords: int, M: int) -> int:
+    """BGEMM_VALU or BGEMM_MFMA: the kernel bgemm() launches for this shape."""
+    k = _int()
+    ctx.check(_lib.bitgnn_ctx_bgemm_kernel(ctx.handle, n, kwords, M, ctypes.byref(k)))
+    return k.value
+
+
+def ctx_reserve(ctx: Context, nbytes: int):
+    ctx.check(_lib.bitgnn_ctx_reserve(ctx.handle, nbytes))
+
+
+def ctx_workspace(ctx: Context) -> int:
+    b = ctypes.c_size_t()
+    ctx.check(_lib.bitgnn_ctx_workspace(ctx.handle, ctypes.byref(b)))
+    return b.value
+
+
+def adj_workspace_bytes(ctx: Context, adj: Optional["Adjacency"], c_max: int, m_max: int) -> int:
+    b = ctypes.c_size_t()
+    ctx.check(_lib.bitgnn_adj_workspace_bytes(adj.handle if adj else None, c_max, m_max,
+                                              ctypes.byref(b)))
+    return b.value
 
 
 def ctx_kernel_timing(ctx: Context, enable: bool):
@@ -438,6 +474,9 @@ class BinaryGNN:
             mw = max(words(d) for d in dims[1:-1]) if len(dims) > 2 else 1
             self.tmp_bits = torch.zeros((n, mw), dtype=torch.int64, device=dev)
             self.tmp_i32 = torch.empty((n, m_last), dtype=torch.int32, device=dev)
+        # set-up: the aggregation workspace for this model's widest layer (the layer calls
+        # themselves never allocate)
+        ctx_reserve(ctx, adj_workspace_bytes(ctx, adj, min(2048, max(dims)), max(dims)))
         torch.cuda.synchronize()
 
     def forward(self, x_f32: torch.Tensor) -> torch.Tensor:

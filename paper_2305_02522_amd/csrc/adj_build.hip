@@ -182,6 +182,63 @@ __global__ void order_from_keys_kernel(const uint64_t *__restrict__ keys, uint32
 
 } // namespace
 
+// Second half of the build, on a handle that already owns the CSR arrays (the caller
+// destroys the handle when this fails): degree-order column slots, row segments.
+static int adj_finish(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
+{
+    const int64_t N = adj->n;
+    const uint32_t nnz = (uint32_t)adj->nnz;
+    // CSR-only and larger than a cache: column ids in degree-order slots.  On a power-law
+    // graph a few percent of the nodes take half of all gathers; in a degree-ordered copy of
+    // the activations their rows are adjacent and stay in L2.
+    if (!adj->blk && nnz > 0 && N >= 65536) {
+        DevBuf rank, col_slot;
+        BG_HIP(ctx, rank.alloc((size_t)N * 4));
+        BG_HIP(ctx, col_slot.alloc((size_t)nnz * 4));
+        rank_kernel<<<blocks_for(N, 256), 256, 0, s>>>(adj->order, (uint32_t)N, rank.as<int32_t>());
+        col_slot_kernel<<<blocks_for(nnz, 256), 256, 0, s>>>(adj->col, nnz, rank.as<int32_t>(),
+                                                            col_slot.as<int32_t>());
+        BG_LAUNCH_CHECK(ctx, "col_slot");
+        BG_HIP(ctx, hipStreamSynchronize(s));
+        adj->col_slot = (int32_t *)col_slot.release();
+        adj->device_bytes += (size_t)nnz * 4;
+    }
+    // segments of the long rows for the CSR bit-SpMM
+    if (N > 0) {
+        DevBuf nseg, seg_slot, cnt;
+        BG_HIP(ctx, nseg.alloc(((size_t)N + 1) * 4));
+        BG_HIP(ctx, cnt.alloc(4));
+        BG_HIP(ctx, hipMemsetAsync(cnt.p, 0, 4, s));
+        adj->seg_len = (int64_t)nnz >= kSegLargeNnz ? kSegLenLarge : kSegLenSmall;
+        seg_count_kernel<<<blocks_for(N + 1, 256), 256, 0, s>>>(
+            adj->order, adj->deg, (uint32_t)N, adj->seg_len, nseg.as<uint32_t>(),
+            cnt.as<uint32_t>());
+        BG_LAUNCH_CHECK(ctx, "seg_count");
+        DevBuf sws;
+        BG_HIP(ctx, sws.alloc(scan_ws_words((uint64_t)N + 1) * 4));
+        scan_inplace(nseg.as<uint32_t>(), (uint32_t)N + 1, sws.as<uint32_t>(), s);
+        uint32_t n_long = 0, n_long_segs = 0;
+        BG_HIP(ctx, hipMemcpyAsync(&n_long, cnt.p, 4, hipMemcpyDeviceToHost, s));
+        BG_HIP(ctx, hipStreamSynchronize(s));
+        if (n_long > 0) {
+            BG_HIP(ctx, hipMemcpyAsync(&n_long_segs, nseg.as<uint32_t>() + n_long, 4,
+                                       hipMemcpyDeviceToHost, s));
+            BG_HIP(ctx, hipStreamSynchronize(s));
+            BG_HIP(ctx, seg_slot.alloc((size_t)n_long_segs * 4));
+            seg_slot_kernel<<<blocks_for(n_long, 256), 256, 0, s>>>(nseg.as<uint32_t>(), n_long,
+                                                                   seg_slot.as<uint32_t>());
+            BG_LAUNCH_CHECK(ctx, "seg_slot");
+            BG_HIP(ctx, hipStreamSynchronize(s));
+            adj->seg_slot = (uint32_t *)seg_slot.release();
+            adj->seg_ptr = (uint32_t *)nseg.release(); // the first n_long + 1 entries are used
+            adj->device_bytes += ((size_t)N + 1) * 4 + (size_t)n_long_segs * 4;
+        }
+        adj->n_long = n_long;
+        adj->n_long_segs = n_long_segs;
+    }
+    return BITGNN_OK;
+}
+
 extern "C" int bitgnn_adj_build(bitgnn_ctx *ctx, void *stream, const int32_t *src,
                                 const int32_t *dst, int64_t E, int64_t N, uint32_t flags,
                                 bitgnn_adj **out)
@@ -299,55 +356,25 @@ extern "C" int bitgnn_adj_build(bitgnn_ctx *ctx, void *stream, const int32_t *sr
             return rc;
         }
     }
-    // CSR-only and larger than a cache: column ids in degree-order slots.  On a power-law
-    // graph a few percent of the nodes take half of all gathers; in a degree-ordered copy of
-    // the activations their rows are adjacent and stay in L2.
-    if (!adj->blk && nnz > 0 && N >= 65536) {
-        DevBuf rank, col_slot;
-        BG_HIP(ctx, rank.alloc((size_t)N * 4));
-        BG_HIP(ctx, col_slot.alloc((size_t)nnz * 4));
-        rank_kernel<<<blocks_for(N, 256), 256, 0, s>>>(adj->order, (uint32_t)N, rank.as<int32_t>());
-        col_slot_kernel<<<blocks_for(nnz, 256), 256, 0, s>>>(adj->col, nnz, rank.as<int32_t>(),
-                                                            col_slot.as<int32_t>());
-        BG_LAUNCH_CHECK(ctx, "col_slot");
-        BG_HIP(ctx, hipStreamSynchronize(s));
-        adj->col_slot = (int32_t *)col_slot.release();
-        adj->device_bytes += (size_t)nnz * 4;
-    }
-    // segments of the long rows for the CSR bit-SpMM
-    if (N > 0) {
-        DevBuf nseg, seg_slot, cnt;
-        BG_HIP(ctx, nseg.alloc(((size_t)N + 1) * 4));
-        BG_HIP(ctx, cnt.alloc(4));
-        BG_HIP(ctx, hipMemsetAsync(cnt.p, 0, 4, s));
-        adj->seg_len = (int64_t)nnz >= kSegLargeNnz ? kSegLenLarge : kSegLenSmall;
-        seg_count_kernel<<<blocks_for(N + 1, 256), 256, 0, s>>>(
-            adj->order, adj->deg, (uint32_t)N, adj->seg_len, nseg.as<uint32_t>(),
-            cnt.as<uint32_t>());
-        BG_LAUNCH_CHECK(ctx, "seg_count");
-        DevBuf sws;
-        BG_HIP(ctx, sws.alloc(scan_ws_words((uint64_t)N + 1) * 4));
-        scan_inplace(nseg.as<uint32_t>(), (uint32_t)N + 1, sws.as<uint32_t>(), s);
-        uint32_t n_long = 0, n_long_segs = 0;
-        BG_HIP(ctx, hipMemcpyAsync(&n_long, cnt.p, 4, hipMemcpyDeviceToHost, s));
-        BG_HIP(ctx, hipStreamSynchronize(s));
-        if (n_long > 0) {
-            BG_HIP(ctx, hipMemcpyAsync(&n_long_segs, nseg.as<uint32_t>() + n_long, 4,
-                                       hipMemcpyDeviceToHost, s));
-            BG_HIP(ctx, hipStreamSynchronize(s));
-            BG_HIP(ctx, seg_slot.alloc((size_t)n_long_segs * 4));
-            seg_slot_kernel<<<blocks_for(n_long, 256), 256, 0, s>>>(nseg.as<uint32_t>(), n_long,
-                                                                   seg_slot.as<uint32_t>());
-            BG_LAUNCH_CHECK(ctx, "seg_slot");
-            BG_HIP(ctx, hipStreamSynchronize(s));
-            adj->seg_slot = (uint32_t *)seg_slot.release();
-            adj->seg_ptr = (uint32_t *)nseg.release(); // the first n_long + 1 entries are used
-            adj->device_bytes += ((size_t)N + 1) * 4 + (size_t)n_long_segs * 4;
-        }
-        adj->n_long = n_long;
-        adj->n_long_segs = n_long_segs;
+    int rc = adj_finish(ctx, s, adj);
+    // the aggregation workspace for the default widths: compute calls never allocate
+    if (rc == BITGNN_OK)
+        rc = bitgnn_ctx_reserve(ctx, bg_adj_workspace_bytes(adj, kDefaultWsChannels,
+                                                            kDefaultWsClasses));
+    if (rc != BITGNN_OK) {
+        bitgnn_adj_destroy(adj);
+        return rc;
     }
     *out = adj;
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_adj_workspace_bytes(const bitgnn_adj *adj, int32_t C_max, int32_t M_max,
+                                          size_t *bytes)
+{
+    if (!adj || !bytes || C_max < 1 || C_max > 2048 || M_max < 1)
+        return BITGNN_ERR_INVALID_ARG;
+    *bytes = bg_adj_workspace_bytes(adj, C_max, M_max);
     return BITGNN_OK;
 }
 

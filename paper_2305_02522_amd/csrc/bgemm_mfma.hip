@@ -99,8 +99,13 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
     for (int c = tid; c < Mp; c += kMfWaves * 64) {
         const bool c_ok = c < M;
         const int pwc = c_ok ? pw[c] : 0;
-        if (EPI == BITGNN_EPI_THRESH_BITS)
-            colk[c] = c_ok ? T[c] - K + 2 * pwc : 0x7FFFFFFF;
+        if (EPI == BITGNN_EPI_THRESH_BITS) {
+            // |Z| <= K, so thresholds beyond +-(K + 1) decide nothing more: clamped first,
+            // the folded constant cannot overflow
+            int32_t tc = c_ok ? T[c] : 0;
+            tc = tc > K + 1 ? K + 1 : (tc < -K - 1 ? -K - 1 : tc);
+            colk[c] = c_ok ? tc - K + 2 * pwc : 0x7FFFFFFF;
+        }
         else
             colk[c] = K - 2 * pwc;
         colf[c] = (EPI == BITGNN_EPI_SCALE_F32 && c_ok) ? alpha[c] : 0.0f;
@@ -269,10 +274,9 @@ int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, 
     const int32_t ldw = kwords * 64 + kMfPad, Mp = (M + 15) / 16 * 16;
     const size_t w8_bytes = (size_t)Mp * ldw;
     const size_t lds_bytes = w8_bytes + (size_t)Mp * 8; // + column constants
-    int rc = bg_ws_reserve(ctx, w8_bytes + (size_t)Mp * 4);
-    if (rc != BITGNN_OK)
-        return rc;
-    uint8_t *w8 = (uint8_t *)ctx->ws;
+    BG_REQUIRE(ctx, w8_bytes + (size_t)Mp * 4 <= kBgemmScratchBytes, BITGNN_ERR_UNSUPPORTED,
+               "bitgnn_bgemm: weights too large for the matrix-core kernel's scratch");
+    uint8_t *w8 = (uint8_t *)ctx->bgemm_ws;
     int32_t *pw = (int32_t *)(w8 + w8_bytes);
     bgemm_widen_w_kernel<<<Mp, 256, 0, s>>>((const uint32_t *)wbits, w_stride * 2, kwords * 64, M,
                                             ldw, w8, pw);

@@ -1217,7 +1217,7 @@ static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, con
         bspmm_blk_kernel<PPV, SPWV><<<grid, 64 * SPWV, lds, s>>>(                                 \
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_item, b->sl_desc, b->tile_group,     \
             (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, b->n_wgs,           \
-            ctx->queue, partial);                                                                 \
+            ctx->sc->queue, partial);                                                                 \
         bg_time_end(ctx, s);                                                                      \
     } while (0)
 #define BG_BLK_SPW(PPV)                                                                           \
@@ -1309,11 +1309,11 @@ static int launch_seeds(bitgnn_ctx *ctx, hipStream_t s, int epilogue, const int3
     if (epilogue != BITGNN_EPI_THRESH_BITS)
         return BITGNN_OK;
     const int entries = 2 * P * W32;
-    BG_REQUIRE(ctx, (size_t)entries <= ctx->seed_table_words, BITGNN_ERR_UNSUPPORTED,
+    BG_REQUIRE(ctx, (size_t)entries <= ctx->sc->seed_table_words, BITGNN_ERR_UNSUPPORTED,
                "bitgnn_bspmm: seed table too small");
-    bspmm_seed_kernel<<<(entries + 127) / 128, 128, 0, s>>>(T, C, W32, P, ctx->seed_table);
+    bspmm_seed_kernel<<<(entries + 127) / 128, 128, 0, s>>>(T, C, W32, P, ctx->sc->seed_table);
     BG_LAUNCH_CHECK(ctx, "bspmm_seed");
-    *seeds = ctx->seed_table;
+    *seeds = ctx->sc->seed_table;
     return BITGNN_OK;
 }
 
@@ -1328,26 +1328,26 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     PermuteAux aux{};
     const uint32_t *seeds = nullptr;
     if (epilogue == BITGNN_EPI_THRESH_BITS) {
-        BG_REQUIRE(ctx, (size_t)(2 * P * W32) <= ctx->seed_table_words, BITGNN_ERR_UNSUPPORTED,
+        BG_REQUIRE(ctx, (size_t)(2 * P * W32) <= ctx->sc->seed_table_words, BITGNN_ERR_UNSUPPORTED,
                    "bitgnn_bspmm: seed table too small");
         aux.kind = 1;
         aux.T = T;
         aux.C = C;
         aux.W32 = W32;
         aux.P = P;
-        aux.table = ctx->seed_table;
-        seeds = ctx->seed_table;
+        aux.table = ctx->sc->seed_table;
+        seeds = ctx->sc->seed_table;
     }
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
     const size_t part_bytes = (size_t)b->n_vrows * part_planes_for(b) * 16;
-    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes);
+    int rc = bg_ws_need(ctx, hperm_bytes + part_bytes, "bitgnn_bspmm");
     if (rc != BITGNN_OK)
         return rc;
-    uint4 *hperm = (uint4 *)ctx->ws;
-    uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
+    uint4 *hperm = (uint4 *)ctx->sc->ws;
+    uint4 *partial = (uint4 *)((char *)ctx->sc->ws + hperm_bytes);
     const uint32_t *h32 = (const uint32_t *)hbits;
     for (int win = 0; win * 4 < W32; ++win) {
-        launch_permute(s, adj, h32, h_stride * 2, win * 4, W32, hperm, ctx->queue,
+        launch_permute(s, adj, h32, h_stride * 2, win * 4, W32, hperm, ctx->sc->queue,
                        win == 0 ? aux : PermuteAux{});
         rc = launch_blk(ctx, s, adj, hperm, partial);
         if (rc != BITGNN_OK)
@@ -1389,12 +1389,13 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
         ((size_t)b->n_vrows * part_planes_for(b) * 16 + 255) & ~(size_t)255;
     const int32_t Mpad = (M + 15) / 16 * 16;
     const size_t w8_bytes = (size_t)nwin * Mpad * 128;
-    int rc = bg_ws_reserve(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)nwin * Mpad * 4);
+    int rc = bg_ws_need(ctx, hperm_bytes + part_bytes + w8_bytes + (size_t)nwin * Mpad * 4,
+                        "bitgnn_gcn_out_layer");
     if (rc != BITGNN_OK)
         return rc;
-    uint4 *hperm = (uint4 *)ctx->ws;
-    uint4 *partial = (uint4 *)((char *)ctx->ws + hperm_bytes);
-    int8_t *w8 = (int8_t *)ctx->ws + hperm_bytes + part_bytes;
+    uint4 *hperm = (uint4 *)ctx->sc->ws;
+    uint4 *partial = (uint4 *)((char *)ctx->sc->ws + hperm_bytes);
+    int8_t *w8 = (int8_t *)ctx->sc->ws + hperm_bytes + part_bytes;
     int32_t *wsum = (int32_t *)(w8 + w8_bytes);
     // the projection's +-1 byte weights are produced by extra workgroups of the first
     // permute launch
@@ -1415,7 +1416,7 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
         ++NB;
     for (int win = 0; win < nwin; ++win) {
         launch_permute(s, adj, (const uint32_t *)hbits, h_stride * 2, win * 4, W32, hperm,
-                       ctx->queue, win == 0 ? aux : PermuteAux{});
+                       ctx->sc->queue, win == 0 ? aux : PermuteAux{});
         rc = launch_blk(ctx, s, adj, hperm, partial);
         if (rc != BITGNN_OK)
             return rc;
@@ -1444,6 +1445,36 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
         BG_LAUNCH_CHECK(ctx, "bspmm_merge_project");
     }
     return BITGNN_OK;
+}
+
+// Context workspace the aggregations on this graph use at most, for up to C aggregated
+// channels (bit rows) and M output classes (integer rows / class projection): the largest
+// of what the four launchers below and above lay out.
+size_t bg_adj_workspace_bytes(const bitgnn_adj *adj, int32_t C, int32_t M)
+{
+    const size_t W32 = ((size_t)C + 31) / 32;
+    size_t need = 0;
+    // CSR bit-SpMM: degree-ordered copy of the rows + bit-sliced counts of the segments
+    {
+        const size_t perm = adj->col_slot ? (((size_t)adj->n * W32 * 4 + 255) & ~(size_t)255) : 0;
+        int seg_planes = 1;
+        while ((1u << seg_planes) <= adj->seg_len)
+            ++seg_planes;
+        need = perm + (size_t)adj->n_long_segs * seg_planes * W32 * 4;
+    }
+    // integer aggregation: int32 sums of the segments
+    const size_t i32 = (size_t)adj->n_long_segs * (size_t)M * 4;
+    need = i32 > need ? i32 : need;
+    if (adj->blk) { // blocked form: one 128-channel window of rows + partial planes (+ the
+                    // class projection's byte weights and column sums)
+        const size_t hperm = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
+        const size_t part =
+            ((size_t)adj->blk->n_vrows * part_planes_for(adj->blk) * 16 + 255) & ~(size_t)255;
+        const size_t nwin = (W32 + 3) / 4, Mpad = ((size_t)M + 15) / 16 * 16;
+        const size_t blk = hperm + part + nwin * Mpad * 128 + nwin * Mpad * 4;
+        need = blk > need ? blk : need;
+    }
+    return need;
 }
 
 // Rough time models (microseconds, fitted on MI355X) of the two aggregation paths.  The
@@ -1512,18 +1543,18 @@ static int launch_bspmm_path(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *a
         ++seg_planes;
     const size_t seg_bytes = (size_t)adj->n_long_segs * seg_planes * W32 * 4;
     if (perm_bytes + seg_bytes) {
-        const int rc = bg_ws_reserve(ctx, perm_bytes + seg_bytes);
+        const int rc = bg_ws_need(ctx, perm_bytes + seg_bytes, "bitgnn_bspmm");
         if (rc != BITGNN_OK)
             return rc;
     }
     const RowSegments seg{adj->seg_ptr,  adj->seg_slot, adj->n_long, adj->n_long_segs,
-                          adj->seg_len,  seg_planes,    (uint32_t *)((char *)ctx->ws + perm_bytes)};
+                          adj->seg_len,  seg_planes,    (uint32_t *)((char *)ctx->sc->ws + perm_bytes)};
     if (adj->col_slot) { // gather from a degree-ordered copy of the rows
         csr_permute_kernel<<<(unsigned)pgrid, kBlock, 0, s>>>(h32, hs32, adj->order,
                                                               (uint32_t)adj->n, W32,
-                                                              (uint32_t *)ctx->ws);
+                                                              (uint32_t *)ctx->sc->ws);
         BG_LAUNCH_CHECK(ctx, "csr_permute");
-        h32 = (const uint32_t *)ctx->ws;
+        h32 = (const uint32_t *)ctx->sc->ws;
         hs32 = W32;
         col = adj->col_slot;
     }
@@ -1589,6 +1620,11 @@ extern "C" int bitgnn_adj_tune(bitgnn_ctx *ctx, void *stream, bitgnn_adj *adj, i
         return BITGNN_OK;
     hipStream_t s = (hipStream_t)stream;
     const int64_t cw = ((int64_t)C + 63) / 64;
+    { // a set-up call: it may grow the workspace
+        const int rc_ws = bitgnn_ctx_reserve(ctx, bg_adj_workspace_bytes(adj, C, 1));
+        if (rc_ws != BITGNN_OK)
+            return rc_ws;
+    }
     TuneBuf h, out, T;
     BG_HIP(ctx, h.alloc((size_t)adj->n * cw * 8));
     BG_HIP(ctx, out.alloc((size_t)adj->n * cw * 8));
@@ -1679,12 +1715,12 @@ int bg_launch_spmm_i32(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, co
     const int64_t grid = ((vrows << lpr_log2) + kBlock - 1) / kBlock;
     BG_REQUIRE(ctx, grid < (1ll << 31), BITGNN_ERR_UNSUPPORTED, "bitgnn_spmm_i32: N too large");
     if (adj->n_long_segs) {
-        const int rc = bg_ws_reserve(ctx, (size_t)adj->n_long_segs * M * 4);
+        const int rc = bg_ws_need(ctx, (size_t)adj->n_long_segs * M * 4, "bitgnn_spmm_i32");
         if (rc != BITGNN_OK)
             return rc;
     }
     const RowSegments seg{adj->seg_ptr, adj->seg_slot, adj->n_long, adj->n_long_segs,
-                          adj->seg_len, 0,             (uint32_t *)ctx->ws};
+                          adj->seg_len, 0,             (uint32_t *)ctx->sc->ws};
     const unsigned grid_long =
         (unsigned)((((uint64_t)adj->n_long << lpr_log2) + kBlock - 1) / kBlock);
     // wide rows that can be read 4 or 2 values per lane: several neighbours per gather

@@ -11,32 +11,47 @@
 
 #define BITGNN_WAVE 64
 
+// Device scratch the aggregation kernels work in: the context's own (allocated by the
+// set-up calls), or the library's static array for the entry point that allocates nothing.
+struct bg_scratch {
+    uint32_t *queue;      // device words: [0] work counter of the blocked bit-SpMM,
+                          // [kFusedBarrierWord] arrival counter of the fused kernel's barriers
+    uint32_t *seed_table; // bit-SpMM threshold seeds
+    size_t seed_table_words;
+    // degree-ordered activations, partial counters of row parts and segments; sized by
+    // bitgnn_adj_workspace_bytes, allocated by bitgnn_ctx_reserve / bitgnn_adj_build only
+    void *ws;
+    size_t ws_bytes;
+};
+
 struct bitgnn_ctx {
     int device;           // -1: validation-only context
     int n_cus;            // compute units of the device
-    int bgemm_path;       // 0: choose per shape, 1: VALU kernel, 2: matrix-core kernel
-                          // (environment BITGNN_BGEMM=valu|mfma at context creation)
-    uint32_t *queue;      // device words: [0] work counter of the blocked bit-SpMM,
-                          // [kFusedBarrierWord] arrival counter of the fused kernel's barriers
+    int bgemm_path;       // BITGNN_BGEMM_AUTO / _VALU / _MFMA (bitgnn_ctx_set_bgemm_path)
+    void *bgemm_ws;       // device scratch of the matrix-core BMM: widened weights and their
+                          // popcounts (fixed size, allocated with the context)
+    bg_scratch own;       // the context's scratch
+    bg_scratch *sc;       // the scratch the current call uses (&own outside such a call)
     uint32_t fused_spin_limit; // polls of one barrier wait before it is abandoned
     char err[256];
-    uint32_t *seed_table; // device scratch of the bit-SpMM threshold seeds
-    size_t seed_table_words;
     // tuning of the column-blocked aggregation format (bitgnn_ctx_set_tuning)
     int32_t cb_nodes;       // nodes per LDS-resident column block (<= 8192)
     int32_t part_len;       // longest run of neighbours one lane accumulates (<= 1023)
     int32_t min_avg_degree; // graphs sparser than this keep the plain CSR path only
-    // grow-only device workspace of the blocked bit-SpMM (permuted activations,
-    // per-part partial counters)
-    void *ws;
-    size_t ws_bytes;
     // optional HIP-event timing of the main aggregation kernel (bitgnn_ctx_kernel_timing)
     int timing;
     int n_timed;
     hipEvent_t tev[2 * 256];
 };
 
+// Largest seed table the bit-SpMM may ask for: 2 parities x 26 planes x 64 words.
+static const size_t kSeedTableWords = 2 * 26 * 64;
 static const int kMaxTimed = 256;
+// Scratch of the matrix-core BMM: at most 144 KB of widened weights (its LDS limit) plus
+// one popcount per padded weight row.
+static const size_t kBgemmScratchBytes = 144 * 1024 + 16 * 1024;
+// Widths bitgnn_adj_build reserves workspace for.
+static const int32_t kDefaultWsChannels = 256, kDefaultWsClasses = 64;
 static const int kFusedBarrierWord = 16; // its own 64-byte line of ctx->queue
 // Brackets one kernel launch with events when timing is on (no-ops otherwise).
 static inline void bg_time_begin(bitgnn_ctx *ctx, hipStream_t s)
@@ -187,7 +202,10 @@ void bg_free_blocked(bitgnn_blocked *b);
 int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj,
                             const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
                             const int32_t *T, void *out, int64_t out_stride);
-int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes);
+int bg_ws_need(bitgnn_ctx *ctx, size_t bytes, const char *who);
+// Bytes of context workspace the aggregations on `adj` need for up to C aggregated
+// channels and M output classes.
+size_t bg_adj_workspace_bytes(const bitgnn_adj *adj, int32_t C, int32_t M);
 // Whether the blocked form is expected to beat the CSR kernel for rows of `bytes_per_nnz`
 // gathered bytes per non-zero, handled in `passes` passes of the blocked kernel.
 // `longest_chain`: neighbours the CSR kernel in question walks serially at most.

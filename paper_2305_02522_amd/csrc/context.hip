@@ -3,9 +3,6 @@
 
 #include <stdlib.h>
 
-// Largest seed table the bit-SpMM may ask for: 2 parities x 26 planes x 64 words.
-static const size_t kSeedTableWords = 2 * 26 * 64;
-
 extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
 {
     if (!out || device < -1)
@@ -18,8 +15,7 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
     ctx->part_len = 255;
     ctx->min_avg_degree = 8;
     ctx->fused_spin_limit = 1u << 22;
-    if (const char *e = getenv("BITGNN_BGEMM"))
-        ctx->bgemm_path = !strcmp(e, "valu") ? 1 : !strcmp(e, "mfma") ? 2 : 0;
+    ctx->sc = &ctx->own;
     if (device >= 0) {
         int count = 0;
         hipError_t e = hipGetDeviceCount(&count);
@@ -31,16 +27,22 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
         if (e == hipSuccess)
             e = hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, device);
         if (e == hipSuccess)
-            e = hipMalloc((void **)&ctx->queue, 256);
+            e = hipMalloc((void **)&ctx->own.queue, 256);
         if (e == hipSuccess)
-            e = hipMemset(ctx->queue, 0, 256);
+            e = hipMemset(ctx->own.queue, 0, 256);
         if (e == hipSuccess)
-            e = hipMalloc((void **)&ctx->seed_table, kSeedTableWords * sizeof(uint32_t));
+            e = hipMalloc((void **)&ctx->own.seed_table, kSeedTableWords * sizeof(uint32_t));
+        if (e == hipSuccess)
+            e = hipMalloc(&ctx->bgemm_ws, kBgemmScratchBytes);
         if (e != hipSuccess) {
+            if (ctx->own.queue)
+                (void)hipFree(ctx->own.queue);
+            if (ctx->own.seed_table)
+                (void)hipFree(ctx->own.seed_table);
             free(ctx);
             return BITGNN_ERR_HIP;
         }
-        ctx->seed_table_words = kSeedTableWords;
+        ctx->own.seed_table_words = kSeedTableWords;
     }
     *out = ctx;
     return BITGNN_OK;
@@ -50,12 +52,14 @@ extern "C" void bitgnn_ctx_destroy(bitgnn_ctx *ctx)
 {
     if (!ctx)
         return;
-    if (ctx->seed_table)
-        (void)hipFree(ctx->seed_table);
-    if (ctx->queue)
-        (void)hipFree(ctx->queue);
-    if (ctx->ws)
-        (void)hipFree(ctx->ws);
+    if (ctx->own.seed_table)
+        (void)hipFree(ctx->own.seed_table);
+    if (ctx->own.queue)
+        (void)hipFree(ctx->own.queue);
+    if (ctx->bgemm_ws)
+        (void)hipFree(ctx->bgemm_ws);
+    if (ctx->own.ws)
+        (void)hipFree(ctx->own.ws);
     for (int i = 0; i < 2 * kMaxTimed; ++i)
         if (ctx->tev[i])
             (void)hipEventDestroy(ctx->tev[i]);
@@ -81,21 +85,63 @@ extern "C" int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t 
     return BITGNN_OK;
 }
 
-// Grow-only workspace; not safe to call while the stream is being captured.
-int bg_ws_reserve(bitgnn_ctx *ctx, size_t bytes)
+extern "C" int bitgnn_ctx_set_bgemm_path(bitgnn_ctx *ctx, int path)
 {
-    if (bytes <= ctx->ws_bytes)
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_REQUIRE(ctx, path >= BITGNN_BGEMM_AUTO && path <= BITGNN_BGEMM_MFMA, BITGNN_ERR_INVALID_ARG,
+               "bitgnn_ctx_set_bgemm_path: path=%d (0 auto, 1 VALU, 2 matrix cores)", path);
+    ctx->bgemm_path = path;
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_ctx_bgemm_kernel(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int32_t M,
+                                       int *kernel)
+{
+    if (!ctx || !kernel || n < 0 || kwords < 1 || M < 1)
+        return BITGNN_ERR_INVALID_ARG;
+    *kernel = bg_bgemm_mfma_applies(ctx, n, kwords, M) ? BITGNN_BGEMM_MFMA : BITGNN_BGEMM_VALU;
+    return BITGNN_OK;
+}
+
+// The aggregation workspace.  Only this set-up call (and bitgnn_adj_build, through it)
+// allocates: it may synchronize the device to replace a smaller workspace.
+extern "C" int bitgnn_ctx_reserve(bitgnn_ctx *ctx, size_t bytes)
+{
+    if (!ctx)
+        return BITGNN_ERR_INVALID_ARG;
+    BG_NEED_DEVICE(ctx);
+    if (bytes <= ctx->own.ws_bytes)
         return BITGNN_OK;
-    if (ctx->ws) {
+    if (ctx->own.ws) {
         BG_HIP(ctx, hipDeviceSynchronize());
-        BG_HIP(ctx, hipFree(ctx->ws));
-        ctx->ws = nullptr;
-        ctx->ws_bytes = 0;
+        BG_HIP(ctx, hipFree(ctx->own.ws));
+        ctx->own.ws = nullptr;
+        ctx->own.ws_bytes = 0;
     }
     bytes = (bytes + (1u << 20)) & ~(size_t)((1u << 20) - 1);
-    BG_HIP(ctx, hipMalloc(&ctx->ws, bytes));
-    ctx->ws_bytes = bytes;
+    BG_HIP(ctx, hipMalloc(&ctx->own.ws, bytes));
+    ctx->own.ws_bytes = bytes;
     return BITGNN_OK;
+}
+
+extern "C" int bitgnn_ctx_workspace(const bitgnn_ctx *ctx, size_t *bytes)
+{
+    if (!ctx || !bytes)
+        return BITGNN_ERR_INVALID_ARG;
+    *bytes = ctx->own.ws_bytes;
+    return BITGNN_OK;
+}
+
+// Compute calls never allocate: a workspace that is too small is an error.
+int bg_ws_need(bitgnn_ctx *ctx, size_t bytes, const char *who)
+{
+    if (bytes <= ctx->sc->ws_bytes)
+        return BITGNN_OK;
+    return bitgnn_fail(ctx, BITGNN_ERR_WORKSPACE,
+                       "%s: needs %zu bytes of workspace, %zu available "
+                       "(bitgnn_adj_workspace_bytes + bitgnn_ctx_reserve)",
+                       who, bytes, ctx->sc->ws_bytes);
 }
 
 extern "C" int bitgnn_ctx_kernel_timing(bitgnn_ctx *ctx, int enable)

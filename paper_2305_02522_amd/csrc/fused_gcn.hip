@@ -436,7 +436,7 @@ extern "C" int bitgnn_gcn2_fused(bitgnn_ctx *ctx, void *stream, const bitgnn_adj
     const int64_t useful = (n + kFusedWaves - 1) / kFusedWaves; // one row per wavefront
     if (blocks > useful)
         blocks = useful;
-    uint32_t *counter = ctx->queue + kFusedBarrierWord;
+    uint32_t *counter = ctx->own.queue + kFusedBarrierWord;
     // four rows per phase-1 step once a wavefront would otherwise walk more than two steps
     const bool rows4 = (n + 1) / 2 > 2 * blocks * kFusedWaves;
 #define BG_FUSED2(TV, RV)                                                                         \

@@ -320,22 +320,26 @@ namespace {
 
 // int32 rows -> int16 rows in place (the int16 row starts where the int32 row did): one
 // wavefront per row reads a 64-channel tile, then writes it; the bytes a tile's write
-// covers belong to tiles already read.
-__global__ __launch_bounds__(256) void narrow_rows_kernel(int32_t *__restrict__ z, int64_t n,
-                                                          int32_t M, int64_t ld32)
+// covers belong to this tile's first half or to tiles already read.  The two views of the
+// row alias on purpose: the destination type says so, and compiler barriers keep every
+// tile's load in front of its store and the store in front of the next tile's load.
+typedef int16_t __attribute__((may_alias)) i16_alias;
+__global__ __launch_bounds__(256) void narrow_rows_kernel(int32_t *z, int64_t n, int32_t M,
+                                                          int64_t ld32)
 {
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (row >= n)
         return;
-    int32_t *src = z + row * ld32;
-    int16_t *dst = (int16_t *)src;
+    const volatile int32_t *src = z + row * ld32;
+    i16_alias *dst = (i16_alias *)(z + row * ld32);
     for (int32_t c0 = 0; c0 < M; c0 += 64) {
         const int32_t c = c0 + lane;
         const int32_t v = c < M ? src[c] : 0;
-        // the store uses the loaded value, so it is issued after the whole tile has arrived
+        asm volatile("" ::: "memory"); // the whole tile is loaded (one instruction) ...
         if (c < M)
-            dst[c] = (int16_t)v;
+            dst[c] = (int16_t)v; // ... before any lane stores (the store waits for the load)
+        asm volatile("" ::: "memory");
     }
 }
 

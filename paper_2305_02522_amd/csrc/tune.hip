@@ -107,6 +107,12 @@ extern "C" int bitgnn_gcn_layer_tune(bitgnn_ctx *ctx, void *stream, const bitgnn
     hipStream_t s = (hipStream_t)stream;
     const int32_t kw = (K + 63) / 64;
     const int64_t mw = ((int64_t)M + 63) / 64;
+    { // a set-up call: it may grow the aggregation workspace
+        const int rc_ws =
+            bitgnn_ctx_reserve(ctx, bg_adj_workspace_bytes(adj, M > 2048 ? 2048 : M, M));
+        if (rc_ws != BITGNN_OK)
+            return rc_ws;
+    }
     TuneMem x, w, tmp_bits, out, tmp_f32, vecs;
     BG_HIP(ctx, x.alloc((size_t)n * kw * 8));
     BG_HIP(ctx, w.alloc((size_t)M * kw * 8));

@@ -141,6 +141,27 @@ def test_chain_check_types_the_papers_recipes(vctx):
     assert _code(B.gcn_layer_tune, vctx, None, 64, 64, 3) == B.ERR_INVALID_ARG
 
 
+def test_workspace_and_bgemm_path_calls(vctx):
+    """The set-up calls of the workspace contract and the BMM kernel choice validate on the
+    host: no compute call allocates, so a caller sizes and reserves the workspace first."""
+    assert _code(B.adj_workspace_bytes, vctx, None, 128, 41) == B.ERR_INVALID_ARG   # no handle
+    assert _code(B.ctx_reserve, vctx, 1 << 20) == B.ERR_NO_DEVICE
+    assert B.ctx_workspace(vctx) == 0
+    assert _code(B.ctx_set_bgemm_path, vctx, 3) == B.ERR_INVALID_ARG
+    assert _code(B.ctx_set_bgemm_path, vctx, -1) == B.ERR_INVALID_ARG
+    # the choice is a host-side rule: matrix cores from 65,536 rows on when the weights fit
+    assert B.ctx_bgemm_kernel(vctx, 1000, 2, 128) == B.BGEMM_VALU
+    assert B.ctx_bgemm_kernel(vctx, 232965, 2, 128) == B.BGEMM_MFMA
+    assert B.ctx_bgemm_kernel(vctx, 232965, 32, 128) == B.BGEMM_VALU     # K = 2048: not in LDS
+    B.ctx_set_bgemm_path(vctx, B.BGEMM_VALU)
+    assert B.ctx_bgemm_kernel(vctx, 232965, 2, 128) == B.BGEMM_VALU
+    B.ctx_set_bgemm_path(vctx, B.BGEMM_MFMA)
+    assert B.ctx_bgemm_kernel(vctx, 1000, 2, 128) == B.BGEMM_MFMA
+    B.ctx_set_bgemm_path(vctx, B.BGEMM_AUTO)
+    assert _code(B.ctx_bgemm_kernel, vctx, 10, 0, 5) == B.ERR_INVALID_ARG
+    assert B.ERR_WORKSPACE == -8
+
+
 def test_ctx_create_rejects_bad_device():
     with pytest.raises(B.BitgnnError):
         B.Context(-2)

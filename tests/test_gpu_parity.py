@@ -35,17 +35,9 @@ TUNINGS = {"default": (8192, 255, 8), "csr-only": (8192, 255, 1 << 30),
 def gemm_ctx(request, B):
     """Contexts that choose the BMM kernel per shape, or always take the VALU / the
     matrix-core kernel (the latter falls back when the weights do not fit in LDS)."""
-    import os
-    old = os.environ.get("BITGNN_BGEMM")
-    if request.param == "auto":
-        os.environ.pop("BITGNN_BGEMM", None)
-    else:
-        os.environ["BITGNN_BGEMM"] = request.param
     c = B.Context(0)
-    if old is None:
-        os.environ.pop("BITGNN_BGEMM", None)
-    else:
-        os.environ["BITGNN_BGEMM"] = old
+    B.ctx_set_bgemm_path(c, {"auto": B.BGEMM_AUTO, "valu": B.BGEMM_VALU,
+                             "mfma": B.BGEMM_MFMA}[request.param])
     yield c
     c.close()
 
@@ -213,6 +205,14 @@ def test_bgemm_three_epilogues(B, gemm_ctx, n, K, M):
     B.bgemm(ctx, xb, n, kw, K, kw, wb, M, kw, B.EPI_THRESH_BITS, dev(t), None, ob, mw)
     torch.cuda.synchronize()
     assert np.array_equal(words_np(ob), orc.to_words(orc.rebin(z, t)))       # pad bits 0
+    # thresholds at and beyond the range of Z (|Z| <= K) and at the int32 limits
+    ext = np.array([np.iinfo(np.int32).min, np.iinfo(np.int32).max, K + 1, -K - 1, K, -K,
+                    np.iinfo(np.int32).max - 1, np.iinfo(np.int32).min + 1], dtype=np.int64)
+    t2 = ext[r.integers(0, len(ext), size=M)].astype(np.int32)
+    ob.fill_(-1)
+    B.bgemm(ctx, xb, n, kw, K, kw, wb, M, kw, B.EPI_THRESH_BITS, dev(t2), None, ob, mw)
+    torch.cuda.synchronize()
+    assert np.array_equal(words_np(ob), orc.to_words(orc.rebin(z, t2)))
     # SCALE
     alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
     of = torch.zeros((n, M), dtype=torch.float32, device="cuda")
@@ -803,6 +803,72 @@ def test_forward_ops_equals_forward(B, ctx):
         assert torch.equal(a, b)
         adj.close()
 
+
+
+# ------------------------------------------------------------------ boundary: no allocation
+@pytest.mark.parametrize("tuning", ["default", "blocked-small", "csr-only"])
+def test_layer_calls_capture_into_a_hip_graph_on_a_fresh_context(B, tuning):
+    """Compute calls only enqueue: the first aggregation ever issued on a context may be
+    recorded into a HIP graph (nothing allocates or synchronizes under capture), and every
+    replay gives the oracle's bits and logits."""
+    c = B.Context(0)
+    B.ctx_set_tuning(c, *TUNINGS[tuning])
+    adj, rp, col, r = _graph(B, c, 6000, 90000, SYM_LOOPS, 4711, hubs=1)
+    dims = [200, 128, 41]
+    layers = W.model_params(r, "gcn", dims)
+    x = W.pm1(r, (6000, dims[0])).astype(np.float32)
+    model = B.BinaryGNN(c, "gcn", adj, dims, layers)         # set-up: reserves the workspace
+    ref, hidden = orc.forward("gcn", rp, col, orc.bin_f32(x), layers, return_hidden=True)
+    xd = dev(x)
+    torch.cuda.synchronize()
+    before = B.ctx_workspace(c)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.forward(xd)                                    # first aggregation: under capture
+    assert B.ctx_workspace(c) == before
+    for rep in range(3):
+        model.act[1].zero_()
+        model.logits.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(words_np(model.act[1])[:, :2], orc.to_words(hidden[0])), rep
+        assert rel_close(model.logits.cpu().numpy(), ref), rep
+        eager = model.forward(xd)                            # eager work between the replays
+        torch.cuda.synchronize()
+        assert rel_close(eager.cpu().numpy(), ref)
+    del graph
+    adj.close()
+    c.close()
+
+
+def test_compute_calls_report_a_workspace_that_is_too_small(B):
+    """A call that needs more workspace than was reserved fails with ERR_WORKSPACE instead of
+    allocating; after bitgnn_ctx_reserve it runs and is right."""
+    c = B.Context(0)
+    B.ctx_set_tuning(c, *TUNINGS["blocked-small"])
+    n, K, M = 500, 64, 9000                                  # 9,000 classes: 1.2 MB of weights
+    adj, rp, col, r = _graph(B, c, n, 4000, SYM_LOOPS, 321)
+    v = W.pm1(r, (n, K))
+    w = W.pm1(r, (K, M))
+    alpha = r.uniform(0.5, 1.5, M).astype(np.float32)
+    need = B.adj_workspace_bytes(c, adj, K, M)
+    assert need > B.ctx_workspace(c)
+    tmp = torch.zeros((n, M), dtype=torch.int32, device="cuda")
+    out = torch.zeros((n, M), dtype=torch.float32, device="cuda")
+    args = (c, adj, _pack_host(v), 1, K, 1, _pack_host(np.ascontiguousarray(w.T)), M, 1,
+            dev(alpha), tmp, out, M)
+    with pytest.raises(B.BitgnnError) as e:
+        B.gcn_out_layer(*args)
+    assert e.value.code == B.ERR_WORKSPACE and "bitgnn_ctx_reserve" in str(e.value)
+    B.ctx_reserve(c, need)
+    assert B.ctx_workspace(c) >= need
+    B.gcn_out_layer(*args)
+    torch.cuda.synchronize()
+    y = orc.spmm_i64(rp, col, orc.bmm(v, w))
+    assert rel_close(out.cpu().numpy(), orc.scale(y, alpha))
+    adj.close()
+    c.close()
 
 # ------------------------------------------------------------------ whole model, one launch
 def _fused_case(B, ctx, n, e, dims, flags, seed, hubs=0, real_features=True):
