@@ -237,6 +237,22 @@ int bitgnn_bspmm(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj, const uin
                  int32_t C, int64_t h_stride, int epilogue, const int32_t *T, void *out,
                  int64_t out_stride);
 
+/* bitgnn_bspmm for callers that cannot allocate device memory at all: code recorded under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as bitgnn_bspmm, but every scratch buffer of the kernels
+ * (work counter, threshold seeds, degree-ordered activation rows, partial counters) lies
+ * in a static device array of BITGNN_STATIC_SCRATCH_BYTES that each GPU the library runs
+ * on holds until the process ends; neither this call nor anything it launches allocates,
+ * frees or synchronizes, and the context's own workspace is not used.
+ * Limit: bitgnn_adj_workspace_bytes(adj, C, 1) must fit in the array minus 16 KB of fixed
+ * tables, else BITGNN_ERR_UNSUPPORTED (message gives both sizes).
+ * All calls on one GPU, from any context, share that GPU's array: calls that overlap in
+ * time on one GPU race; run them one after the other on a stream. */
+#define BITGNN_STATIC_SCRATCH_BYTES (32u << 20)
+int bitgnn_bspmm_static(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                        const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
+                        const int32_t *T, void *out, int64_t out_stride);
+
 /* Aggregation of integer activations over the 0/1 adjacency (the last layer's
  * BSpMM.FBF of the binary-aggregation model, kept in exact integers):
  * Y[i][c] = sum_{j in N(i)} Z[j][c], c < M.  Z: int32 [N][z_stride].

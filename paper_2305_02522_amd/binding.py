@@ -73,6 +73,7 @@ _SIGNATURES = {
                                     _vp, _vp, _i64]),
     "bitgnn_adj_tune": (_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "bitgnn_bspmm": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
+    "bitgnn_bspmm_static": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _int, _vp, _vp, _i64]),
     "bitgnn_spmm_i32": (_int, [_vp, _vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _i64]),
     "bitgnn_spmm_f32": (_int, [_vp, _vp, _vp, _vp, _int, _i32, _i64, _vp, _vp, _int, _vp, _vp,
                                _i64]),
@@ -291,6 +292,17 @@ def gcn_layer_f32(ctx: Context, adj, x, K, ldx, tau, wbits, M, w_stride, T_mm, T
 def bspmm(ctx: Context, adj: Optional[Adjacency], hbits, C, h_stride, epilogue, T, out, out_stride):
     ctx.check(_lib.bitgnn_bspmm(ctx.handle, _stream(), adj.handle if adj else None, _ptr(hbits), C,
                                 h_stride, epilogue, _ptr(T), _ptr(out), out_stride))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def bspmm_static(ctx: Context, adj: Optional[Adjacency], hbits, C, h_stride, epilogue, T, out,
+                 out_stride):
+    """bspmm() with every scratch buffer in the library's static device array."""
+    ctx.check(_lib.bitgnn_bspmm_static(ctx.handle, _stream(), adj.handle if adj else None,
+                                       _ptr(hbits), C, h_stride, epilogue, _ptr(T), _ptr(out),
+                                       out_stride))
 
 
 def spmm_i32(ctx: Context, adj: Optional[Adjacency], Z, M, z_stride, z_abs_bound, alpha, out,

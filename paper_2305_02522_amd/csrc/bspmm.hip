@@ -1684,6 +1684,66 @@ extern "C" int bitgnn_bspmm(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj
                            out_stride);
 }
 
+// ---------------------------------------------------------------------------
+// The same aggregation for callers that cannot allocate (code under HIP graph capture,
+// tight serving loops): every scratch buffer of the kernels -- work counter, threshold
+// seeds, degree-ordered activation rows, partial counters of row parts and segments --
+// lives in one static device array, so the call touches no allocator at all.  Each GPU
+// holds its own copy of the array until the process ends; its address is looked up once
+// per device and kept (the array's name itself is only a host-side stand-in).
+namespace {
+constexpr size_t kStaticQueueBytes = 256;
+constexpr size_t kStaticSeedBytes = (kSeedTableWords * 4 + 255) & ~(size_t)255;
+constexpr size_t kStaticHeadBytes = kStaticQueueBytes + kStaticSeedBytes;
+constexpr size_t kStaticScratchBytes = BITGNN_STATIC_SCRATCH_BYTES;
+static_assert(kStaticScratchBytes > kStaticHeadBytes && kStaticScratchBytes % 256 == 0, "layout");
+constexpr int kMaxStaticDevices = 64;
+} // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void *g_static_scratch[kMaxStaticDevices]; // device address of `scratch`, per device
+
+// Set-up: called by bitgnn_ctx_create with the context's device current.
+int bg_static_scratch_init(bitgnn_ctx *ctx)
+{
+    if (ctx->device < 0 || ctx->device >= kMaxStaticDevices || g_static_scratch[ctx->device])
+        return BITGNN_OK;
+    void *ptr = nullptr;
+    BG_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    g_static_scratch[ctx->device] = ptr;
+    return BITGNN_OK;
+}
+
+extern "C" int bitgnn_bspmm_static(bitgnn_ctx *ctx, void *stream, const bitgnn_adj *adj,
+                                   const uint64_t *hbits, int32_t C, int64_t h_stride,
+                                   int epilogue, const int32_t *T, void *out, int64_t out_stride)
+{
+    int rc = bg_check_bspmm(ctx, adj, hbits, C, h_stride, epilogue, T, out, out_stride);
+    if (rc != BITGNN_OK)
+        return rc;
+    BG_NEED_DEVICE(ctx);
+    BG_REQUIRE(ctx, ctx->device < kMaxStaticDevices && g_static_scratch[ctx->device],
+               BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm_static: no static scratch on device %d",
+               ctx->device);
+    const size_t avail = kStaticScratchBytes - kStaticHeadBytes;
+    const size_t need = bg_adj_workspace_bytes(adj, C, 1);
+    BG_REQUIRE(ctx, need <= avail, BITGNN_ERR_UNSUPPORTED,
+               "bitgnn_bspmm_static: this graph needs %zu bytes of scratch, the static array "
+               "holds %zu (use bitgnn_bspmm)",
+               need, avail);
+    unsigned char *base = (unsigned char *)g_static_scratch[ctx->device];
+    bg_scratch st;
+    st.queue = (uint32_t *)base;
+    st.seed_table = (uint32_t *)(base + kStaticQueueBytes);
+    st.seed_table_words = kSeedTableWords;
+    st.ws = base + kStaticHeadBytes;
+    st.ws_bytes = avail;
+    ctx->sc = &st; // the kernels take these pointers exactly as they take the context's
+    rc = bg_launch_bspmm(ctx, (hipStream_t)stream, adj, hbits, C, h_stride, epilogue, T, out,
+                         out_stride);
+    ctx->sc = &ctx->own;
+    return rc;
+}
+
 int bg_check_spmm_i32(bitgnn_ctx *ctx, const bitgnn_adj *adj, const int32_t *Z, int32_t M,
                       int64_t z_stride, int64_t z_abs_bound, const void *out, int64_t out_stride)
 {

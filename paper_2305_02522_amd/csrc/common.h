@@ -203,6 +203,7 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
                             const uint64_t *hbits, int32_t C, int64_t h_stride, int epilogue,
                             const int32_t *T, void *out, int64_t out_stride);
 int bg_ws_need(bitgnn_ctx *ctx, size_t bytes, const char *who);
+int bg_static_scratch_init(bitgnn_ctx *ctx);
 // Bytes of context workspace the aggregations on `adj` need for up to C aggregated
 // channels and M output classes.
 size_t bg_adj_workspace_bytes(const bitgnn_adj *adj, int32_t C, int32_t M);

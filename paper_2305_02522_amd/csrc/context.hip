@@ -43,6 +43,10 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
             return BITGNN_ERR_HIP;
         }
         ctx->own.seed_table_words = kSeedTableWords;
+        if (bg_static_scratch_init(ctx) != BITGNN_OK) {
+            bitgnn_ctx_destroy(ctx);
+            return BITGNN_ERR_HIP;
+        }
     }
     *out = ctx;
     return BITGNN_OK;
