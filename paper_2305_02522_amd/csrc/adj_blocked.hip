@@ -55,7 +55,8 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 // slot numbering, degrees in slot order, parts per row
 __global__ void slot_kernel(const int32_t *__restrict__ order, const int32_t *__restrict__ deg,
                             uint32_t n, int part_len, int32_t *__restrict__ rank,
-                            uint32_t *__restrict__ deg_sorted, uint32_t *__restrict__ nparts)
+                            uint32_t *__restrict__ deg_sorted, uint32_t *__restrict__ nparts,
+                            uint32_t *__restrict__ n_multi)
 {
     const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s > n)
@@ -71,6 +72,8 @@ __global__ void slot_kernel(const int32_t *__restrict__ order, const int32_t *__
     deg_sorted[s] = d;
     const uint32_t np = (d + part_len - 1) / part_len;
     nparts[s] = np ? np : 1u;
+    if (np > 1) // rows are in decreasing degree order: these are the first *n_multi slots
+        atomicAdd(n_multi, 1u);
 }
 
 // keys (row slot << cbits | column slot), one wavefront per row
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(256) void blocked_keys_kernel(
 __global__ void vrow_kernel(const uint64_t *__restrict__ skeys, const uint32_t *__restrict__ rp2,
                             const uint32_t *__restrict__ vptr, uint32_t n, int cbits, int cbn,
                             uint32_t *__restrict__ v_beg, uint32_t *__restrict__ v_end,
-                            uint64_t *__restrict__ vkeys)
+                            uint32_t *__restrict__ v_slot, uint64_t *__restrict__ vkeys)
 {
     const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= n)
@@ -110,6 +113,7 @@ __global__ void vrow_kernel(const uint64_t *__restrict__ skeys, const uint32_t *
         const uint32_t v = v0 + p;
         v_beg[v] = b;
         v_end[v] = e;
+        v_slot[v] = s | (np == 1 ? 0x80000000u : 0u); // bit 31: the row's only part
         vkeys[v] = (lo << 52) | (hi << 40) | ((uint64_t)(1023u - len) << 30) | v;
     }
 }
@@ -242,13 +246,18 @@ __global__ void tail_group_kernel(uint16_t *__restrict__ idx16, uint32_t G, int 
         idx16[(uint64_t)G * 64 * kGroupSteps + i] = (uint16_t)cbn;
 }
 
-// part id (row-major: the parts of a row are consecutive) of every processing position
-__global__ void part_vid_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
-                                uint32_t *__restrict__ part_vid)
+// per processing position: {part id (row-major: the parts of a row are consecutive ids)
+// | bit 31 if it is the row's only part, node id of the row}
+__global__ void part_info_kernel(const uint64_t *__restrict__ svkeys, uint32_t V,
+                                 const uint32_t *__restrict__ v_slot,
+                                 const int32_t *__restrict__ order, uint2 *__restrict__ part_info)
 {
     const uint32_t pos = blockIdx.x * blockDim.x + threadIdx.x;
-    if (pos < V)
-        part_vid[pos] = (uint32_t)svkeys[pos] & kVidMask;
+    if (pos < V) {
+        const uint32_t v = (uint32_t)svkeys[pos] & kVidMask;
+        const uint32_t sl = v_slot[v];
+        part_info[pos] = make_uint2(v | (sl & 0x80000000u), (uint32_t)order[sl & 0x7FFFFFFFu]);
+    }
 }
 
 __global__ void wg_range_kernel(const uint32_t *__restrict__ sl_cb, uint32_t S, uint32_t W,
@@ -332,7 +341,7 @@ void bg_free_blocked(bitgnn_blocked *b)
     (void)hipFree(b->tile_group);
     (void)hipFree(b->idx16);
     (void)hipFree(b->row_vptr);
-    (void)hipFree(b->part_vid);
+    (void)hipFree(b->part_info);
     free(b);
 }
 
@@ -349,7 +358,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     while ((1ll << cbits) < adj->n)
         ++cbits;
 
-    DevBuf rank, deg_sorted, nparts, keys_a, keys_b, hist, scan_ws;
+    DevBuf rank, deg_sorted, nparts, keys_a, keys_b, hist, scan_ws, multi;
     const uint32_t sort_n = nnz > n ? nnz : n;
     const uint32_t sort_tiles = (sort_n + kSortTile - 1) / kSortTile;
     BG_HIP(ctx, rank.alloc((size_t)n * 4));
@@ -365,9 +374,11 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                   : (uint64_t)n + 1;
     BG_HIP(ctx, scan_ws.alloc(scan_ws_words(scan_max) * 4));
 
+    BG_HIP(ctx, multi.alloc(4));
+    BG_HIP(ctx, hipMemsetAsync(multi.p, 0, 4, s));
     slot_kernel<<<blocks_for((int64_t)n + 1, 256), 256, 0, s>>>(
         adj->order, adj->deg, n, part_len, rank.as<int32_t>(), deg_sorted.as<uint32_t>(),
-        nparts.as<uint32_t>());
+        nparts.as<uint32_t>(), multi.as<uint32_t>());
     // exclusive scans: rp2 = entry offsets by slot, vptr = first part by slot
     scan_inplace(deg_sorted.as<uint32_t>(), n + 1, scan_ws.as<uint32_t>(), s);
     scan_inplace(nparts.as<uint32_t>(), n + 1, scan_ws.as<uint32_t>(), s);
@@ -380,21 +391,23 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     uint64_t *skeys = radix_sort(keys_a.as<uint64_t>(), keys_b.as<uint64_t>(), nnz, 2 * cbits,
                                  hist.as<uint32_t>(), scan_ws.as<uint32_t>(), s);
     BG_LAUNCH_CHECK(ctx, "blocked radix_sort");
-    uint32_t V = 0;
+    uint32_t V = 0, n_multi = 0;
     BG_HIP(ctx, hipMemcpyAsync(&V, vptr + n, 4, hipMemcpyDeviceToHost, s));
+    BG_HIP(ctx, hipMemcpyAsync(&n_multi, multi.p, 4, hipMemcpyDeviceToHost, s));
     BG_HIP(ctx, hipStreamSynchronize(s));
     if (V >= kVidMask)
         return BITGNN_OK;
 
     // parts, sorted by (first block, last block, decreasing length)
-    DevBuf v_beg, v_end, vk_a, vk_b;
+    DevBuf v_beg, v_end, v_slot, vk_a, vk_b;
     BG_HIP(ctx, v_beg.alloc((size_t)V * 4));
     BG_HIP(ctx, v_end.alloc((size_t)V * 4));
+    BG_HIP(ctx, v_slot.alloc((size_t)V * 4));
     BG_HIP(ctx, vk_a.alloc((size_t)V * 8));
     BG_HIP(ctx, vk_b.alloc((size_t)V * 8));
     vrow_kernel<<<blocks_for(n, 256), 256, 0, s>>>(skeys, rp2, vptr, n, cbits, cbn,
                                                   v_beg.as<uint32_t>(), v_end.as<uint32_t>(),
-                                                  vk_a.as<uint64_t>());
+                                                  v_slot.as<uint32_t>(), vk_a.as<uint64_t>());
     BG_LAUNCH_CHECK(ctx, "vrow");
     // V <= nnz + n, so the histogram buffers sized for sort_n suffice when V <= sort_n;
     // V can exceed sort_n only if n > nnz, i.e. never on the graphs that get here
@@ -412,11 +425,11 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     while (spw > 4 && (S + spw - 1) / spw < want)
         spw /= 2;
     const uint32_t W = (S + spw - 1) / spw;
-    DevBuf sl_cb, sl_tile_base, wg_cb, part_vid;
+    DevBuf sl_cb, sl_tile_base, wg_cb, part_info;
     BG_HIP(ctx, sl_cb.alloc((size_t)S * 4));
     BG_HIP(ctx, sl_tile_base.alloc(((size_t)S + 1) * 4));
     BG_HIP(ctx, wg_cb.alloc((size_t)W * 4));
-    BG_HIP(ctx, part_vid.alloc((size_t)V * 4));
+    BG_HIP(ctx, part_info.alloc((size_t)V * 8));
     slice_range_kernel<<<S + 1, 64, 0, s>>>(svkeys, V, S, sl_cb.as<uint32_t>(),
                                             sl_tile_base.as<uint32_t>());
     scan_inplace(sl_tile_base.as<uint32_t>(), S + 1, scan_ws.as<uint32_t>(), s);
@@ -458,7 +471,8 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
                                        sl_tile_base.as<uint32_t>(), tile_group.as<uint32_t>(),
                                        idx16.as<uint16_t>());
     BG_LAUNCH_CHECK(ctx, "tile fill");
-    part_vid_kernel<<<blocks_for(V, 256), 256, 0, s>>>(svkeys, V, part_vid.as<uint32_t>());
+    part_info_kernel<<<blocks_for(V, 256), 256, 0, s>>>(svkeys, V, v_slot.as<uint32_t>(),
+                                                       adj->order, part_info.as<uint2>());
     wg_range_kernel<<<blocks_for(W, 256), 256, 0, s>>>(sl_cb.as<uint32_t>(), S, W, spw,
                                                       wg_cb.as<uint32_t>());
     BG_LAUNCH_CHECK(ctx, "wg_range");
@@ -484,6 +498,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     bitgnn_blocked *b = (bitgnn_blocked *)calloc(1, sizeof(bitgnn_blocked));
     BG_REQUIRE(ctx, b, BITGNN_ERR_INVALID_ARG, "bitgnn_adj_build: out of host memory");
     b->cbn = cbn;
+    b->n_multi = n_multi;
     b->ncb = (int32_t)ncb;
     b->part_len = part_len;
     b->forced = ctx->min_avg_degree == 0;
@@ -494,13 +509,13 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     b->n_tiles = T;
     b->n_groups = G;
     b->device_bytes = ((size_t)G + 1) * kGroupIds * 2 + ((size_t)T + 1) * 4 + (size_t)S * 16 +
-                      (size_t)W * 8 + ((size_t)n + 1) * 4 + (size_t)V * 4;
+                      (size_t)W * 8 + ((size_t)n + 1) * 4 + (size_t)V * 8;
     b->wg_item = (uint2 *)wg_item.release();
     b->sl_desc = (uint4 *)sl_desc.release();
     b->tile_group = (uint32_t *)tile_group.release();
     b->idx16 = (uint16_t *)idx16.release();
     b->row_vptr = (uint32_t *)nparts.release();
-    b->part_vid = (uint32_t *)part_vid.release();
+    b->part_info = (uint2 *)part_info.release();
     adj->blk = b;
     adj->device_bytes += b->device_bytes;
     return BITGNN_OK;

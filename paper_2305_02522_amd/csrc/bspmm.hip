@@ -592,10 +592,11 @@ __device__ __forceinline__ void project_weights_entry(int c, int win, int t,
 // a launch of its own: the threshold seeds of the merge, or the projection's weights.
 struct PermuteAux {
     int kind; // 0 none, 1 seeds, 2 projection weights
-    // seeds
+    // seeds: of the merge (P planes) and of the rows the aggregation kernel finishes itself
+    // (PF planes; 0: none)
     const int32_t *T;
-    int32_t C, W32, P;
-    uint32_t *table;
+    int32_t C, W32, P, PF;
+    uint32_t *table, *table_fin;
     // projection weights
     const uint32_t *w32;
     int64_t w_stride32;
@@ -613,9 +614,13 @@ __global__ __launch_bounds__(256) void blk_permute_kernel(
 {
     if (blockIdx.x >= permute_blocks) { // workgroup-uniform: the set-up work's own workgroups
         const int vb = (int)(blockIdx.x - permute_blocks);
-        if (aux.kind == 1)
-            seed_entry(vb * 256 + (int)threadIdx.x, aux.T, aux.C, aux.W32, aux.P, aux.table);
-        else if (aux.kind == 2)
+        if (aux.kind == 1) {
+            const int e = vb * 256 + (int)threadIdx.x, n_merge = 2 * aux.P * aux.W32;
+            if (e < n_merge)
+                seed_entry(e, aux.T, aux.C, aux.W32, aux.P, aux.table);
+            else if (aux.PF)
+                seed_entry(e - n_merge, aux.T, aux.C, aux.W32, aux.PF, aux.table_fin);
+        } else if (aux.kind == 2)
             project_weights_entry(vb % aux.Mpad, vb / aux.Mpad, (int)threadIdx.x, aux.w32,
                                   aux.w_stride32, aux.K, aux.M, aux.Mpad, aux.w8, aux.wsum);
         return;
@@ -725,6 +730,18 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// What the kernel needs to finish rows that consist of a single part itself (threshold
+// epilogue only): such a row's count is complete in the lane, so it is compared and stored
+// there and then (Algorithm 1's final test and store) and never travels as partial planes.
+struct BlkFinish {
+    int enabled;
+    const int32_t *deg;     // [n] by node id
+    const uint32_t *seeds;  // [2][PP + 2][W32] threshold seeds of the part counters
+    void *out;              // packed output rows
+    int64_t out_stride;     // in 64-bit words
+    int32_t C, W32, win;
+};
+
 // Launched with one workgroup per compute unit (its LDS block leaves room for one
 // only).  Every workgroup takes work items (kSlicesPerWg slices each, heaviest first)
 // from an atomic counter until the list is exhausted: a compute unit that finishes
@@ -738,8 +755,9 @@ template <int PP, int SPW>
 __global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
     const uint4 *__restrict__ hperm, uint32_t n, uint32_t cbn, const uint2 *__restrict__ wg_item,
     const uint4 *__restrict__ sl_desc, const uint32_t *__restrict__ tile_group,
-    const uint32_t *__restrict__ idx, const uint32_t *__restrict__ part_vid, uint32_t S,
-    uint32_t V, uint32_t n_items, uint32_t *__restrict__ queue, uint4 *__restrict__ partial)
+    const uint32_t *__restrict__ idx, const uint2 *__restrict__ part_info, uint32_t S,
+    uint32_t V, uint32_t n_items, uint32_t *__restrict__ queue, uint4 *__restrict__ partial,
+    BlkFinish fin)
 {
     extern __shared__ uint4 hblk[]; // cbn rows + 16 all-zero rows (one per bank group)
     __shared__ uint32_t s_next;
@@ -773,7 +791,11 @@ __global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
         uint32_t g = it.g;
         const uint32_t pos = it.slice * 64 + lane;
         const bool writes = it.has && pos < V;
-        const uint32_t vid = part_vid[writes ? pos : 0u]; // needed at the end only
+        const uint2 pinfo = part_info[writes ? pos : 0u]; // needed at the end only
+        const uint32_t vid = pinfo.x & 0x3FFFFFFFu;
+        const bool single = fin.enabled && (pinfo.x >> 31);
+        // degree of a row this lane finishes itself (requested now, used at the end)
+        const uint32_t fdeg = (writes && single) ? (uint32_t)fin.deg[pinfo.y] : 0u;
         uint32_t acc[PP][4], pend[PP][4];
 #pragma unroll
         for (int p = 0; p < PP; ++p)
@@ -886,6 +908,28 @@ __global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
                 carry = nc;
             }
         }
+        // A row that is one part is complete here: add the threshold seed, compare, store
+        // the packed bits (its count fits PP planes, the seeded count PP + 2).
+        if (writes && single) {
+            constexpr int PF = PP + 2;
+            const uint32_t row = pinfo.y;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int w = fin.win * 4 + q;
+                if (w < fin.W32) {
+                    uint32_t a[PF], sd[PF];
+#pragma unroll
+                    for (int p = 0; p < PF; ++p) {
+                        a[p] = p < PP ? acc[p < PP ? p : 0][q] : 0u;
+                        sd[p] = fin.seeds[((fdeg & 1u) * PF + p) * fin.W32 + w];
+                    }
+                    planes_add<PF>(a, sd);
+                    bspmm_epilogue<PF, BITGNN_EPI_THRESH_BITS>(a, fdeg, row, w, fin.W32, fin.C,
+                                                               fin.out, fin.out_stride);
+                }
+            }
+        }
+        const bool stores = writes && !single;
         // Partial planes are filed under the part id, so that the merge reads the parts of
         // a row, and of consecutive rows, back to back.  A lane storing its own 8 planes
         // would touch 64 different 128-byte lines with every store instruction; instead the
@@ -903,11 +947,11 @@ __global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
                 const int src = r * (64 / PP) + lane / PP; // the part whose line this lane helps store
                 const uint4 v = stage[src * PP + lane % PP];
                 const uint32_t svid = (uint32_t)__shfl((int)vid, src, 64);
-                const int swr = __shfl((int)writes, src, 64);
+                const int swr = __shfl((int)stores, src, 64);
                 if (swr)
                     partial[(uint64_t)svid * PP + lane % PP] = v;
             }
-        } else if (writes) {
+        } else if (stores) {
 #pragma unroll
             for (int p = 0; p < PP; ++p)
                 partial[(uint64_t)vid * PP + p] =
@@ -1173,37 +1217,43 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
     }
 }
 
+// Merges the parts of the first `rows` rows in degree order (all rows, or only those of
+// several parts when the aggregation kernel finished the others itself).
 template <int P, int PP>
 void launch_merge_pp(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
-                     int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
-                     int64_t out_stride)
+                     uint32_t rows, int win, int32_t C, int32_t W32, const uint32_t *seeds,
+                     void *out, int64_t out_stride)
 {
     const bitgnn_blocked *b = adj->blk;
-    const unsigned grid = (unsigned)(((uint64_t)adj->n * 4 + kBlock - 1) / kBlock);
+    const unsigned grid = (unsigned)(((uint64_t)rows * 4 + kBlock - 1) / kBlock);
+    if (grid == 0)
+        return;
     if (epilogue == BITGNN_EPI_THRESH_BITS)
         bspmm_merge_kernel<P, BITGNN_EPI_THRESH_BITS, PP><<<grid, kBlock, 0, s>>>(
-            partial32, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n, win, C,
-            W32, seeds, out, out_stride);
+            partial32, b->row_vptr, adj->order, adj->deg, rows, win, C, W32, seeds, out,
+            out_stride);
     else
         bspmm_merge_kernel<P, BITGNN_EPI_RAW_I32, PP><<<grid, kBlock, 0, s>>>(
-            partial32, b->row_vptr, adj->order, adj->deg, (uint32_t)adj->n, win, C,
-            W32, seeds, out, out_stride);
+            partial32, b->row_vptr, adj->order, adj->deg, rows, win, C, W32, seeds, out,
+            out_stride);
 }
 
 template <int P>
 void launch_merge_p(hipStream_t s, int epilogue, const bitgnn_adj *adj, const uint32_t *partial32,
-                    int win, int32_t C, int32_t W32, const uint32_t *seeds, void *out,
-                    int64_t out_stride)
+                    uint32_t rows, int win, int32_t C, int32_t W32, const uint32_t *seeds,
+                    void *out, int64_t out_stride)
 {
     if (part_planes_for(adj->blk) == 8)
-        launch_merge_pp<P, 8>(s, epilogue, adj, partial32, win, C, W32, seeds, out, out_stride);
+        launch_merge_pp<P, 8>(s, epilogue, adj, partial32, rows, win, C, W32, seeds, out,
+                              out_stride);
     else
-        launch_merge_pp<P, 10>(s, epilogue, adj, partial32, win, C, W32, seeds, out, out_stride);
+        launch_merge_pp<P, 10>(s, epilogue, adj, partial32, rows, win, C, W32, seeds, out,
+                               out_stride);
 }
 
 // The aggregation kernel proper; `partial` receives PP planes of 16 bytes per part.
 static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, const uint4 *hperm,
-                      uint4 *partial)
+                      uint4 *partial, const BlkFinish &fin)
 {
     const bitgnn_blocked *b = adj->blk;
     const size_t lds = ((size_t)b->cbn + 16) * 16;
@@ -1216,8 +1266,8 @@ static int launch_blk(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *adj, con
         bg_time_begin(ctx, s);                                                                    \
         bspmm_blk_kernel<PPV, SPWV><<<grid, 64 * SPWV, lds, s>>>(                                 \
             hperm, (uint32_t)adj->n, (uint32_t)b->cbn, b->wg_item, b->sl_desc, b->tile_group,     \
-            (const uint32_t *)b->idx16, b->part_vid, b->n_slices, b->n_vrows, b->n_wgs,           \
-            ctx->sc->queue, partial);                                                                 \
+            (const uint32_t *)b->idx16, b->part_info, b->n_slices, b->n_vrows, b->n_wgs,          \
+            ctx->sc->queue, partial, fin);                                                        \
         bg_time_end(ctx, s);                                                                      \
     } while (0)
 #define BG_BLK_SPW(PPV)                                                                           \
@@ -1295,7 +1345,7 @@ static void launch_permute(hipStream_t s, const bitgnn_adj *adj, const uint32_t 
     const unsigned pb = (unsigned)((adj->n + 255) / 256);
     unsigned extra = 0;
     if (aux.kind == 1)
-        extra = (unsigned)((2 * aux.P * aux.W32 + 255) / 256);
+        extra = (unsigned)((2 * (aux.P + aux.PF) * aux.W32 + 255) / 256);
     else if (aux.kind == 2)
         extra = (unsigned)(aux.Mpad * aux.nwin);
     blk_permute_kernel<<<pb + extra, 256, 0, s>>>(h32, h_stride32, adj->order, (uint32_t)adj->n, w0,
@@ -1324,18 +1374,26 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     const bitgnn_blocked *b = adj->blk;
     const int32_t W32 = (C + 31) / 32;
     const int P = planes_for(adj);
+    const int PF = part_planes_for(b) + 2;
+    // With the threshold epilogue the aggregation kernel finishes the rows that are a single
+    // part itself; only the first n_multi rows (in degree order) have parts to merge.
+    const bool finish = epilogue == BITGNN_EPI_THRESH_BITS;
     // the threshold seeds are computed by extra workgroups of the first permute launch
     PermuteAux aux{};
     const uint32_t *seeds = nullptr;
-    if (epilogue == BITGNN_EPI_THRESH_BITS) {
-        BG_REQUIRE(ctx, (size_t)(2 * P * W32) <= ctx->sc->seed_table_words, BITGNN_ERR_UNSUPPORTED,
-                   "bitgnn_bspmm: seed table too small");
+    uint32_t *seeds_fin = nullptr;
+    if (finish) {
+        BG_REQUIRE(ctx, (size_t)(2 * (P + PF) * W32) <= ctx->sc->seed_table_words,
+                   BITGNN_ERR_UNSUPPORTED, "bitgnn_bspmm: seed table too small");
+        seeds_fin = ctx->sc->seed_table + 2 * P * W32;
         aux.kind = 1;
         aux.T = T;
         aux.C = C;
         aux.W32 = W32;
         aux.P = P;
+        aux.PF = PF;
         aux.table = ctx->sc->seed_table;
+        aux.table_fin = seeds_fin;
         seeds = ctx->sc->seed_table;
     }
     const size_t hperm_bytes = (((size_t)adj->n * 16) + 255) & ~(size_t)255;
@@ -1346,28 +1404,38 @@ int bg_launch_bspmm_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_adj *ad
     uint4 *hperm = (uint4 *)ctx->sc->ws;
     uint4 *partial = (uint4 *)((char *)ctx->sc->ws + hperm_bytes);
     const uint32_t *h32 = (const uint32_t *)hbits;
+    const uint32_t merge_rows = finish ? b->n_multi : (uint32_t)adj->n;
     for (int win = 0; win * 4 < W32; ++win) {
         launch_permute(s, adj, h32, h_stride * 2, win * 4, W32, hperm, ctx->sc->queue,
                        win == 0 ? aux : PermuteAux{});
-        rc = launch_blk(ctx, s, adj, hperm, partial);
+        BlkFinish fin{};
+        fin.enabled = finish ? 1 : 0;
+        fin.deg = adj->deg;
+        fin.seeds = seeds_fin;
+        fin.out = out;
+        fin.out_stride = out_stride;
+        fin.C = C;
+        fin.W32 = W32;
+        fin.win = win;
+        rc = launch_blk(ctx, s, adj, hperm, partial, fin);
         if (rc != BITGNN_OK)
             return rc;
         switch (P) {
         case 12:
-            launch_merge_p<12>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
-                               out, out_stride);
+            launch_merge_p<12>(s, epilogue, adj, (const uint32_t *)partial, merge_rows, win, C,
+                               W32, seeds, out, out_stride);
             break;
         case 16:
-            launch_merge_p<16>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
-                               out, out_stride);
+            launch_merge_p<16>(s, epilogue, adj, (const uint32_t *)partial, merge_rows, win, C,
+                               W32, seeds, out, out_stride);
             break;
         case 20:
-            launch_merge_p<20>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
-                               out, out_stride);
+            launch_merge_p<20>(s, epilogue, adj, (const uint32_t *)partial, merge_rows, win, C,
+                               W32, seeds, out, out_stride);
             break;
         default:
-            launch_merge_p<26>(s, epilogue, adj, (const uint32_t *)partial, win, C, W32, seeds,
-                               out, out_stride);
+            launch_merge_p<26>(s, epilogue, adj, (const uint32_t *)partial, merge_rows, win, C,
+                               W32, seeds, out, out_stride);
             break;
         }
         BG_LAUNCH_CHECK(ctx, "bspmm_merge");
@@ -1417,7 +1485,7 @@ int bg_launch_agg_project_blocked(bitgnn_ctx *ctx, hipStream_t s, const bitgnn_a
     for (int win = 0; win < nwin; ++win) {
         launch_permute(s, adj, (const uint32_t *)hbits, h_stride * 2, win * 4, W32, hperm,
                        ctx->sc->queue, win == 0 ? aux : PermuteAux{});
-        rc = launch_blk(ctx, s, adj, hperm, partial);
+        rc = launch_blk(ctx, s, adj, hperm, partial, BlkFinish{});
         if (rc != BITGNN_OK)
             return rc;
         const int32_t w32w = W32 - win * 4 < 4 ? W32 - win * 4 : 4;

@@ -44,8 +44,9 @@ struct bitgnn_ctx {
     hipEvent_t tev[2 * 256];
 };
 
-// Largest seed table the bit-SpMM may ask for: 2 parities x 26 planes x 64 words.
-static const size_t kSeedTableWords = 2 * 26 * 64;
+// Largest seed tables the bit-SpMM may ask for: 2 parities x 64 words x (26 planes for the
+// merge + 12 planes for the rows the blocked kernel finishes itself).
+static const size_t kSeedTableWords = 2 * (26 + 12) * 64;
 static const int kMaxTimed = 256;
 // Scratch of the matrix-core BMM: at most 144 KB of widened weights (its LDS limit) plus
 // one popcount per padded weight row.
@@ -87,6 +88,7 @@ static const int64_t kSegLargeNnz = 1ll << 24;
 // Column-blocked, length-balanced aggregation format (see adj_blocked.hip).
 struct bitgnn_blocked {
     int32_t cbn;            // nodes per column block
+    uint32_t n_multi;       // rows with more than one part (the first n_multi degree-order slots)
     int32_t ncb;            // column blocks
     int32_t part_len;       // longest row part (sets the planes of the partial counters)
     int32_t forced;         // built with a density threshold of 0: always preferred
@@ -103,7 +105,8 @@ struct bitgnn_blocked {
     uint16_t *idx16;        // [(n_groups + 1) * 64 * kGroupSteps] column ids inside the block;
                             // cbn = "none"; the last group is padding that a prefetch may read
     uint32_t *row_vptr;     // [n + 1] by degree-order slot: first part of the row
-    uint32_t *part_vid;     // [V] by processing position: part id (a row's parts are consecutive ids)
+    uint2 *part_info;       // [V] by processing position: {part id (a row's parts are consecutive
+                            // ids) | bit 31: the row's only part, node id of the row}
     size_t device_bytes;
 };
 
