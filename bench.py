@@ -28,17 +28,59 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
 VALU_PEAK_TLOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, 32-bit lane-ops
+MFMA_I8_PEAK_TOPS = 5000.0                  # dense int8 matrix cores
+
+
+def source_stamp():
+    """Identifies the aggregation kernels and the format builder the counter summaries under
+    profiles/ were taken with: counters of other code are not this run's."""
+    import hashlib
+    h = hashlib.sha1()
+    for f in ("bspmm.hip", "adj_blocked.hip", "bgemm.hip", "bgemm_mfma.hip"):
+        h.update(open(os.path.join(ROOT, "paper_2305_02522_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def load_counters(cfg, stored_ids):
+    """profiles/bench_cfg<N>_counters.txt: per kernel, figures derived from rocprofv3 --pmc runs
+    of this command (HBM bytes per launch, VALU busy, ...).  Returns {} when the file was
+    taken with other kernel sources or another aggregation format."""
+    path = os.path.join(ROOT, "profiles", f"bench_cfg{cfg}_counters.txt")
+    if not os.path.exists(path):
+        return {}
+    out, ok = {}, False
+    for line in open(path):
+        t = line.split()
+        if line.startswith("# stamp:"):
+            kv = dict(x.split("=") for x in t[2:])
+            ok = kv.get("src") == source_stamp() and int(kv.get("stored_ids", -1)) == stored_ids
+        elif t and t[0] == "kernel" and len(t) >= 2:
+            out[t[1]] = {t[i]: float(t[i + 1]) for i in range(2, len(t) - 1, 2)}
+    return out if ok else {}
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def op_models(wl, nnz, blocked, fused=False):
+def op_models(wl, nnz, blocked, fused=False, bgemm_kernel=None):
     """Per-op work (bit-ops) and algorithmic bytes / lane-ops, keyed like forward_ops labels.
     Index bytes of an aggregation = min(bytes of the format the kernel actually streams,
-    CSR at 4 B per non-zero), so a padded format earns no bandwidth credit."""
+    CSR at 4 B per non-zero), so a padded format earns no bandwidth credit.
+    bgemm_kernel(n, kwords, M) -> "valu" | "mfma": the kernel the library launches for a
+    packed-operand BMM; it sets the op's roofline (vector lane-ops, or int8 matrix-core
+    operations on the bits widened to bytes: 2 N K M)."""
     n = wl.n
+    bgemm_kernel = bgemm_kernel or (lambda rows, kwords, m: "valu")
+
+    def bgemm_op(k_bits, kwords, m, bytes_):
+        op = dict(work=n * k_bits * m, bytes=bytes_)
+        if bgemm_kernel(n, kwords, m) == "mfma":
+            op.update(bound="mfma", mfma_ops=2 * n * kwords * 64 * m, kernel="bgemm_mfma_kernel")
+        else:
+            op.update(bound="alu", lane_ops=2 * n * m * 2 * kwords, kernel="bgemm_kernel")
+        return op
+
     w64 = lambda k: (k + 63) // 64
     idx_bytes = 4 * nnz + 4 * (n + 1)
     if blocked["parts"]:
@@ -77,8 +119,7 @@ def op_models(wl, nnz, blocked, fused=False):
                                               lane_ops=2 * n * m * ((k_in + 31) // 32),
                                               bound="hbm")
             else:
-                ops[f"L{l}.bgemm"] = dict(work=n * k_in * m, bytes=8 * kw * (n + m) + out_b,
-                                          lane_ops=2 * n * m * ((k_in + 31) // 32), bound="alu")
+                ops[f"L{l}.bgemm"] = bgemm_op(k_in, kw, m, 8 * kw * (n + m) + out_b)
             if not last:
                 ops[f"L{l}.bspmm"] = dict(work=nnz * m,
                                           bytes=idx_bytes + 16 * n * w64(m) + 4 * n + 4 * m,
@@ -89,8 +130,7 @@ def op_models(wl, nnz, blocked, fused=False):
                                       bytes=idx_bytes + 16 * n * kw + 4 * n + 4 * k_in,
                                       bound="hbm")
             out_b = 4 * n * m if last else 8 * n * w64(m)
-            ops[f"L{l}.bgemm"] = dict(work=n * 2 * k_in * m, bytes=16 * kw * (n + m) + out_b,
-                                      lane_ops=2 * n * m * 4 * kw, bound="alu")
+            ops[f"L{l}.bgemm"] = bgemm_op(2 * k_in, 2 * kw, m, 16 * kw * (n + m) + out_b)
     return ops
 
 
@@ -268,6 +308,9 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1 << 30,
                     help="rows of the workload the CPU oracle is timed on (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-steps", type=int, default=5,
+                    help="steps of the cache-flushed leg (1.25 GB swept through the caches "
+                    "before each; reported beside the steady-state numbers; 0 = skip)")
     ap.add_argument("--unfused", action="store_true",
                     help="time the layer calls even where the one-launch kernel applies "
                     "(two-layer GCN on a small graph, e.g. --config 1)")
@@ -337,13 +380,16 @@ def main():
     # stream is the stream the library launches on); the library itself brackets its
     # main aggregation kernel with HIP events on the same stream
     labels, events = [], []
+    first_step = [True]
 
     def mark(label):
         ev = torch.cuda.Event(enable_timing=True)
         ev.record()
         events[-1].append(ev)
-        if len(events) == 1:
+        if first_step[0]:
             labels.append(label)
+            if label is None:
+                first_step[0] = False
 
     B.ctx_kernel_timing(ctx, True)
     torch.cuda.synchronize()
@@ -366,7 +412,9 @@ def main():
     blocked = adj.blocked_info()
     if fused:
         assert int(model.fused_status.item()) == 0, "a grid barrier wait was abandoned"
-    models = op_models(wl, adj.nnz, blocked, fused)
+    def bgemm_kernel(rows, kwords, m):
+        return "mfma" if B.ctx_bgemm_kernel(ctx, rows, kwords, m) == B.BGEMM_MFMA else "valu"
+    models = op_models(wl, adj.nnz, blocked, fused, bgemm_kernel)
     total_work = sum(m["work"] for m in models.values())
     value = total_work / (ms_per_step * 1e-3) / 1e9
 
@@ -388,24 +436,49 @@ def main():
         for i, lab in enumerate(agg_labels):
             agg_kernel_ms.setdefault(lab, []).extend(agg_ms[i::len(agg_labels)])
 
+    counters = load_counters(args.config, blocked["stored_ids"])
+
+    def fractions(m, ms, launches=1.0):
+        """Roofline fractions of an op (or of one of its launches) that took `ms`."""
+        f = dict(hbm_frac=round(m["bytes"] / launches / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+        if "lane_ops" in m:
+            f["valu_frac"] = round(m["lane_ops"] / (ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, 4)
+        if "mfma_ops" in m:
+            f["mfma_i8_frac"] = round(m["mfma_ops"] / (ms * 1e-3) / 1e12 / MFMA_I8_PEAK_TOPS, 4)
+        for name, v in f.items():
+            assert v <= 1.0, f"{name} = {v} > 1: the op model does not describe the kernel that ran"
+        return f
+
+    def kernel_name(lab):
+        kind = lab.split(".")[-1]
+        if kind == "bgemm":
+            return models[lab]["kernel"]
+        return {"bspmm": "bspmm_blk_kernel" if took_blocked else "bspmm_kernel",
+                "out_layer": "bspmm_blk_kernel" if lab in agg_kernel_ms else "spmm_i32_kernel",
+                "bgemm_f32": "bgemm_f32_kernel", "gcn2_fused": "gcn2_fused_kernel",
+                "pack_f32": "pack_rows_kernel"}[kind]
+
     kernels = {}
     for lab, ts in per_op.items():
         avg = float(np.mean(ts))
         m = models[lab]
-        k = dict(avg_us=round(avg * 1e3, 2), min_us=round(float(np.min(ts)) * 1e3, 2),
-                 alg_MB=round(m["bytes"] / 1e6, 2),
-                 hbm_frac=round(m["bytes"] / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+        k = dict(kernel=kernel_name(lab), avg_us=round(avg * 1e3, 2),
+                 min_us=round(float(np.min(ts)) * 1e3, 2), alg_MB=round(m["bytes"] / 1e6, 2),
+                 bound=m["bound"], **fractions(m, avg))
         if m["work"]:
             k["Gbit_ops_per_s"] = round(m["work"] / (avg * 1e-3) / 1e9, 1)
-        if "lane_ops" in m:
-            k["valu_frac"] = round(m["lane_ops"] / (avg * 1e-3) / 1e12 / VALU_PEAK_TLOPS, 4)
         if lab in agg_kernel_ms:      # the aggregation kernel alone (sum over channel windows)
             per_call = len(agg_kernel_ms[lab]) / args.steps
             k["agg_kernel_us"] = round(float(np.mean(agg_kernel_ms[lab])) * per_call * 1e3, 2)
+        c = counters.get(k["kernel"])
+        if c:                         # from the rocprofv3 --pmc summaries under profiles/
+            k["counters"] = {key: c[key] for key in ("valu_busy", "lds_busy", "hbm_MB", "l2_hit")
+                             if key in c}
         kernels[lab] = k
 
     # roofline of the dominant kernel: for an aggregation op that is the library-timed
-    # aggregation kernel (one launch), for the other ops the op is a single kernel
+    # aggregation kernel (one launch), for the other ops the op is a single kernel; the
+    # whole call (with its permute / merge launches) is reported beside it
     def kernel_time_ms(lab):
         if lab in agg_kernel_ms:
             return float(np.mean(agg_kernel_ms[lab])), len(agg_kernel_ms[lab]) / args.steps
@@ -413,25 +486,51 @@ def main():
     dom = max(per_op, key=lambda lab: kernel_time_ms(lab)[0] * kernel_time_ms(lab)[1])
     dm = models[dom]
     davg, launches = kernel_time_ms(dom)
-    kname = {"bspmm": "bspmm_blk_kernel" if took_blocked else "bspmm_kernel",
-             "out_layer": "bspmm_blk_kernel" if dom in agg_kernel_ms else "spmm_i32_kernel",
-             "bgemm_f32": "bgemm_f32_kernel", "bgemm": "bgemm_kernel",
-             "gcn2_fused": "gcn2_fused_kernel",
-             "pack_f32": "pack_rows_kernel"}[dom.split(".")[-1]]
+    kname = kernel_name(dom)
+    fr = fractions(dm, davg, launches)
     if dm["bound"] == "hbm":
-        ach = dm["bytes"] / launches / (davg * 1e-3) / 1e9
-        roofline = dict(kernel=kname, op=dom, bound="hbm", achieved=round(ach, 1),
-                        peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4),
-                        avg_launch_us=round(davg * 1e3, 2), traffic=None)
+        ach, peak, unit, frac = fr["hbm_frac"] * HBM_PEAK_GBS, HBM_PEAK_GBS, "GB/s", fr["hbm_frac"]
+    elif dm["bound"] == "mfma":
+        ach, peak, unit, frac = (fr["mfma_i8_frac"] * MFMA_I8_PEAK_TOPS, MFMA_I8_PEAK_TOPS,
+                                 "TOP/s", fr["mfma_i8_frac"])
     else:
-        ach = dm["lane_ops"] / (davg * 1e-3) / 1e12
-        roofline = dict(kernel=kname, op=dom, bound="alu", achieved=round(ach, 2),
-                        peak=round(VALU_PEAK_TLOPS, 2), unit="Tlane-op/s",
-                        frac=round(ach / VALU_PEAK_TLOPS, 4),
-                        avg_launch_us=round(davg * 1e3, 2), traffic=None)
-    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file):
-        roofline["traffic"] = json.load(open(traffic_file)).get(f"cfg{args.config}", {}).get(kname)
+        ach, peak, unit, frac = (fr["valu_frac"] * VALU_PEAK_TLOPS, round(VALU_PEAK_TLOPS, 2),
+                                 "Tlane-op/s", fr["valu_frac"])
+    call_avg = float(np.mean(per_op[dom]))
+    roofline = dict(kernel=kname, op=dom, bound=dm["bound"], achieved=round(ach, 1), peak=peak,
+                    unit=unit, frac=frac, avg_launch_us=round(davg * 1e3, 2),
+                    call={"avg_us": round(call_avg * 1e3, 2), **fractions(dm, call_avg)},
+                    traffic=None)
+    c = counters.get(kname)
+    if c and "hbm_MB" in c:
+        roofline["traffic"] = int(c["hbm_MB"] * 1e6)
+        roofline["valu_busy"] = c.get("valu_busy")
+
+    # cache-flushed leg: the same step with > 1 GB swept through the caches before every
+    # step (the 256 MB Infinity Cache and the L2 then hold none of the operands)
+    cold = None
+    if args.cold_steps > 0:
+        sweep = torch.empty(320 * 1024 * 1024, dtype=torch.float32, device="cuda")  # 1.25 GB
+        cold_ev = []
+        for _ in range(args.cold_steps):
+            sweep.add_(1.0)
+            events.clear()
+            events.append([])
+            run_step(mark)
+            cold_ev.append(events[-1])
+        torch.cuda.synchronize()
+        cold_ops = {lab: [] for lab in per_op}
+        cold_step = []
+        for evs in cold_ev:
+            cold_step.append(evs[0].elapsed_time(evs[-1]))
+            for i, lab in enumerate(labels[:-1]):
+                cold_ops[lab].append(evs[i].elapsed_time(evs[i + 1]))
+        cold = {"steps": args.cold_steps, "flush_MB": round(sweep.numel() * 8 / 1e6),
+                "ms_per_step": round(float(np.mean(cold_step)), 4),
+                "Gbit_edge_ops_per_s": round(total_work / float(np.mean(cold_step)) / 1e6, 1),
+                "kernels_avg_us": {lab: round(float(np.mean(v)) * 1e3, 2)
+                                   for lab, v in cold_ops.items()}}
+        del sweep
 
     result = {
         "metric": "binary GNN layer throughput (Gbit-edge-ops/s) + full-graph inference ms, 1 GPU",
@@ -446,6 +545,8 @@ def main():
                    "aggregation_format": blocked},
         "kernels": kernels, "roofline": roofline,
     }
+    if cold:
+        result["cache_flushed"] = cold
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a row sample ...")
         rate, secs, threads = cpu_baseline(wl, args.cpu_rows)
