@@ -55,7 +55,10 @@ def load_counters(cfg, stored_ids):
             kv = dict(x.split("=") for x in t[2:])
             ok = kv.get("src") == source_stamp() and int(kv.get("stored_ids", -1)) == stored_ids
         elif t and t[0] == "kernel" and len(t) >= 2:
-            out[t[1]] = {t[i]: float(t[i + 1]) for i in range(2, len(t) - 1, 2)}
+            # t[1] = kernel name with its template arguments, e.g. bspmm_blk_kernel<8,16>
+            short, _, targs = t[1].partition("<")
+            out.setdefault(short, {})["<" + targs if targs else ""] = {
+                t[i]: float(t[i + 1]) for i in range(2, len(t) - 1, 2)}
     return out if ok else {}
 
 
@@ -472,8 +475,10 @@ def main():
             k["agg_kernel_us"] = round(float(np.mean(agg_kernel_ms[lab])) * per_call * 1e3, 2)
         c = counters.get(k["kernel"])
         if c:                         # from the rocprofv3 --pmc summaries under profiles/
-            k["counters"] = {key: c[key] for key in ("valu_busy", "lds_busy", "hbm_MB", "l2_hit")
-                             if key in c}
+            pick = lambda v: {key: v[key] for key in ("us", "valu_busy", "lds_busy", "mfma_busy",
+                                                      "hbm_MB", "l2_hit") if key in v}
+            k["counters"] = pick(next(iter(c.values()))) if len(c) == 1 else \
+                {targs: pick(v) for targs, v in c.items()}     # one entry per instantiation
         kernels[lab] = k
 
     # roofline of the dominant kernel: for an aggregation op that is the library-timed
@@ -502,9 +507,12 @@ def main():
                     call={"avg_us": round(call_avg * 1e3, 2), **fractions(dm, call_avg)},
                     traffic=None)
     c = counters.get(kname)
-    if c and "hbm_MB" in c:
-        roofline["traffic"] = int(c["hbm_MB"] * 1e6)
-        roofline["valu_busy"] = c.get("valu_busy")
+    if c:       # the instantiation whose duration is closest to this run's launches
+        v = min(c.values(), key=lambda v: abs(v.get("us", 0.0) - davg * 1e3))
+        roofline["traffic"] = int(v["hbm_MB"] * 1e6)
+        roofline["valu_busy"] = v.get("valu_busy")
+        roofline["traffic_frac_of_hbm_peak"] = round(
+            v["hbm_MB"] * 1e6 / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if v.get("us") else None
 
     # cache-flushed leg: the same step with > 1 GB swept through the caches before every
     # step (the 256 MB Infinity Cache and the L2 then hold none of the operands)
