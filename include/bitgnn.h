@@ -98,11 +98,12 @@ const char *bitgnn_last_error(const bitgnn_ctx *ctx);
  * counterpart of the paper's tuning utilities, Section 3.4).  A graph with at
  * least min_avg_degree stored non-zeros per node also gets a column-blocked form
  * (unless its tiles would pad to more than 6 stored ids per non-zero; 0 forces it)
- * whose activation blocks of cb_nodes nodes (64..8192) are staged in LDS and
+ * whose activation blocks of cb_nodes nodes (64..10208) are staged in LDS and
  * whose rows are cut into parts of at most part_len (4..1023) neighbours (up to
  * 255 the per-part partial counters are one 128-byte line, above it they take
  * 160 bytes); sparser graphs use plain CSR with global-memory gathers.  Results do
- * not depend on these values.  Defaults: 8192, 255, 8. */
+ * not depend on these values.  Defaults: 10208 (with 16 zero rows beside it a block
+ * then fills the 160 KB of LDS), 255, 8. */
 int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
                           int32_t min_avg_degree);
 

@@ -351,8 +351,7 @@ int bg_build_blocked(bitgnn_ctx *ctx, hipStream_t s, bitgnn_adj *adj)
     const uint32_t n = (uint32_t)adj->n, nnz = (uint32_t)adj->nnz;
     const int cbn = ctx->cb_nodes, part_len = ctx->part_len;
     const int64_t ncb = (adj->n + cbn - 1) / cbn;
-    // (the kernel's workgroup copies at most 8 rows of a block per thread)
-    if (ncb > 4095 || nnz == 0 || cbn > 8 * 64 * kSlicesPerWg)
+    if (ncb > 4095 || nnz == 0 || cbn > kMaxCbNodes)
         return BITGNN_OK; // stays on the CSR path
     int cbits = 1;
     while ((1ll << cbits) < adj->n)

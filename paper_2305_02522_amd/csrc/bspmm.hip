@@ -837,7 +837,7 @@ __global__ __launch_bounds__(64 * SPW) void bspmm_blk_kernel(
             // A wavefront copies 64 consecutive rows per instruction, straight from L2 into
             // LDS (no register round trip); the ragged end of the last block goes row by row.
 #pragma unroll
-            for (int k = 0; k < 8 * (kSlicesPerWg / SPW); ++k) {
+            for (int k = 0; k < (kMaxCbNodes + 64 * SPW - 1) / (64 * SPW); ++k) {
                 const uint32_t w0 = (uint32_t)wave * 64u + (uint32_t)k * (64u * SPW); // uniform
                 if (w0 + 64u <= rows) {
                     __builtin_amdgcn_global_load_lds(

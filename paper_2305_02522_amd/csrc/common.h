@@ -35,7 +35,7 @@ struct bitgnn_ctx {
     uint32_t fused_spin_limit; // polls of one barrier wait before it is abandoned
     char err[256];
     // tuning of the column-blocked aggregation format (bitgnn_ctx_set_tuning)
-    int32_t cb_nodes;       // nodes per LDS-resident column block (<= 8192)
+    int32_t cb_nodes;       // nodes per LDS-resident column block (<= kMaxCbNodes)
     int32_t part_len;       // longest run of neighbours one lane accumulates (<= 1023)
     int32_t min_avg_degree; // graphs sparser than this keep the plain CSR path only
     // optional HIP-event timing of the main aggregation kernel (bitgnn_ctx_kernel_timing)
@@ -79,6 +79,8 @@ static_assert(kGroupSteps == 8 || kGroupSteps == 16, "groups of 8 or 16 steps");
 // Slices (wavefronts) per workgroup of the blocked bit-SpMM: 16 on large graphs; 8 or 4
 // where that is what it takes to give every compute unit a work item.
 static const int kSlicesPerWg = 16;
+// most rows of a column block: (rows + 16 zero rows) x 16 bytes fill the 160 KB of LDS
+static const int kMaxCbNodes = 10208;
 
 // Segment lengths of the CSR bit-SpMM (see bitgnn_adj::seg_len) and the non-zero count from
 // which the long one is used.

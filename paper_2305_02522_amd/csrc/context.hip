@@ -11,7 +11,7 @@ extern "C" int bitgnn_ctx_create(bitgnn_ctx **out, int device)
     if (!ctx)
         return BITGNN_ERR_INVALID_ARG;
     ctx->device = device;
-    ctx->cb_nodes = 8192;
+    ctx->cb_nodes = kMaxCbNodes;
     ctx->part_len = 255;
     ctx->min_avg_degree = 8;
     ctx->fused_spin_limit = 1u << 22;
@@ -77,10 +77,10 @@ extern "C" int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t 
 {
     if (!ctx)
         return BITGNN_ERR_INVALID_ARG;
-    BG_REQUIRE(ctx, cb_nodes >= 64 && cb_nodes <= 8192 && part_len >= 4 && part_len <= 1023 &&
+    BG_REQUIRE(ctx, cb_nodes >= 64 && cb_nodes <= kMaxCbNodes && part_len >= 4 && part_len <= 1023 &&
                         min_avg_degree >= 0,
                BITGNN_ERR_INVALID_ARG,
-               "bitgnn_ctx_set_tuning: cb_nodes=%d (64..8192) part_len=%d (4..1023) "
+               "bitgnn_ctx_set_tuning: cb_nodes=%d (64..10208) part_len=%d (4..1023) "
                "min_avg_degree=%d (>= 0)",
                cb_nodes, part_len, min_avg_degree);
     ctx->cb_nodes = cb_nodes;

@@ -26,9 +26,10 @@ def ctx(B):
     c.close()
 
 
-TUNINGS = {"default": (8192, 255, 8), "csr-only": (8192, 255, 1 << 30),
+TUNINGS = {"default": (10208, 255, 8), "csr-only": (10208, 255, 1 << 30),
            "blocked-small": (128, 16, 0), "blocked-long-parts": (64, 1023, 0),
-           "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0)}
+           "blocked-odd": (1000, 100, 0), "blocked-default-sizes": (8192, 512, 0),
+           "blocked-largest-block": (10208, 255, 0)}
 
 
 @pytest.fixture(scope="module", params=["auto", "valu", "mfma"])
@@ -153,7 +154,7 @@ def test_adj_build_matches_set_definition(B, ctx, n, e, flags, seed):
 
 
 def test_tuning_validation(B, ctx):
-    for bad in ((63, 512, 32), (8193, 512, 32), (8192, 3, 32), (8192, 1024, 32), (8192, 512, -1)):
+    for bad in ((63, 512, 32), (10209, 512, 32), (8192, 3, 32), (8192, 1024, 32), (8192, 512, -1)):
         with pytest.raises(B.BitgnnError) as e:
             B.ctx_set_tuning(ctx, *bad)
         assert e.value.code == B.ERR_INVALID_ARG

@@ -33,7 +33,7 @@ def _case(B, ctx, n, e, C, seed):
     return adj, h, t, cw
 
 
-@pytest.mark.parametrize("tuning", [(8192, 255, 8), (8192, 255, 1 << 30), (128, 16, 0)])
+@pytest.mark.parametrize("tuning", [(10208, 255, 8), (10208, 255, 1 << 30), (128, 16, 0)])
 def test_static_scratch_entry_point_equals_bspmm(B, tuning):
     ctx = B.Context(0)
     B.ctx_set_tuning(ctx, *tuning)
