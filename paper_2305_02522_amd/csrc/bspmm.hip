@@ -1064,7 +1064,7 @@ constexpr int kProjWaves = 4;     // wavefronts per workgroup, 16 nodes each
 constexpr int kProjTiles = 4;     // class tiles of 16 per pass (64 classes)
 
 template <int NB, int PP> // digits of 7 bits: max degree < 2^(7 NB)
-__global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
+__global__ __launch_bounds__(kProjWaves * 64, NB <= 2 ? 8 : 4) void bspmm_merge_project_kernel(
     const uint32_t *__restrict__ partial32, const uint32_t *__restrict__ row_vptr,
     const int32_t *__restrict__ order,
     const int32_t *__restrict__ deg, uint32_t n, int32_t W32, const int8_t *__restrict__ w8,
@@ -1095,14 +1095,6 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
         s_wsum[c] = c < M ? wsum[c] : 0;
         s_alpha[c] = c < M ? alpha[c] : 0.0f;
     }
-    long aop[kProjTiles][4];
-#pragma unroll
-    for (int t = 0; t < kProjTiles; ++t)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const int row = t * 16 < M ? t * 16 + (lane & 15) : (lane & 15); // rows padded to 16
-            aop[t][w] = *(const long *)(w8 + (int64_t)row * 128 + 8 * (lane >> 4) + 32 * w);
-        }
 
     // --- merge the parts of 16 nodes (lane = node * 4 + word)
     {
@@ -1129,6 +1121,12 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
 
     // --- digits (lane = node + 16 g): B operands, 8 channels x NB digits per word
     const int nd = lane & 15, g = lane >> 4;
+    // weight operands of one class tile at a time (the next tile's are requested while this
+    // one's products run): holding all four tiles cost 32 registers and half the occupancy
+    long aop[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        aop[w] = *(const long *)(w8 + (int64_t)nd * 128 + 8 * g + 32 * w);
     long bop[4][NB];
     {
         const uint32_t sel01 = (uint32_t)g | ((uint32_t)(4 + g) << 8) | 0x0C0C0000u;
@@ -1152,7 +1150,7 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
 
     // --- contraction with the class weights, 64 classes per pass
     for (int c0 = 0; c0 < M; c0 += kProjTiles * 16) {
-        if (c0 > 0) { // later passes: constants and operands of these 64 classes
+        if (c0 > 0) { // later passes: constants and first operands of these 64 classes
             __syncthreads(); // the previous pass has read s_wsum / s_alpha / s_out
             if (threadIdx.x < kProjTiles * 16) {
                 const int c = c0 + threadIdx.x;
@@ -1160,46 +1158,51 @@ __global__ __launch_bounds__(kProjWaves * 64) void bspmm_merge_project_kernel(
                 s_alpha[threadIdx.x] = c < M ? alpha[c] : 0.0f;
             }
 #pragma unroll
-            for (int t = 0; t < kProjTiles; ++t)
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const int row = c0 + t * 16 < M ? c0 + t * 16 + nd : nd;
-                    aop[t][w] = *(const long *)(w8 + (int64_t)row * 128 + 8 * g + 32 * w);
-                }
+            for (int w = 0; w < 4; ++w)
+                aop[w] = *(const long *)(w8 + (int64_t)(c0 + nd) * 128 + 8 * g + 32 * w);
             __syncthreads();
         }
-        v4i acc[kProjTiles][NB];
+#pragma unroll 1
+        for (int t = 0; t < kProjTiles; ++t) {
+            if (c0 + t * 16 >= M) // wave-uniform
+                break;
+            long nop[4];
+            {
+                // rows of w8 are padded to a multiple of 16 classes; past the last tile the
+                // first tile is read again and not used
+                const bool more = t + 1 < kProjTiles && c0 + (t + 1) * 16 < M;
+                const int nrow = more ? c0 + (t + 1) * 16 + nd : nd;
 #pragma unroll
-        for (int t = 0; t < kProjTiles; ++t)
+                for (int w = 0; w < 4; ++w)
+                    nop[w] = *(const long *)(w8 + (int64_t)nrow * 128 + 8 * g + 32 * w);
+            }
+            v4i acc[NB];
 #pragma unroll
             for (int b = 0; b < NB; ++b)
-                acc[t][b] = (v4i){0, 0, 0, 0};
+                acc[b] = (v4i){0, 0, 0, 0};
 #pragma unroll
-        for (int t = 0; t < kProjTiles; ++t) {
-            if (c0 + t * 16 < M) { // wave-uniform
+            for (int w = 0; w < 4; ++w) {
+                if (w < W32) {
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if (w < W32) {
-#pragma unroll
-                        for (int b = 0; b < NB; ++b)
-                            acc[t][b] = __builtin_amdgcn_mfma_i32_16x16x32_i8(
-                                aop[t][w], bop[w][b], acc[t][b], 0, 0, 0);
-                    }
+                    for (int b = 0; b < NB; ++b)
+                        acc[b] = __builtin_amdgcn_mfma_i32_16x16x32_i8(aop[w], bop[w][b], acc[b], 0,
+                                                                       0, 0);
                 }
             }
-        }
-#pragma unroll
-        for (int t = 0; t < kProjTiles; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int cl = t * 16 + 4 * g + j;
                 int32_t val = 0;
 #pragma unroll
                 for (int b = NB - 1; b >= 0; --b)
-                    val = (val << 7) + acc[t][b][j];
+                    val = (val << 7) + acc[b][j];
                 s_buf[wave][nd * (kProjTiles * 16 + 1) + cl] =
                     (uint32_t)(2 * val - d_nd * s_wsum[cl]);
             }
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                aop[w] = nop[w];
+        }
         __syncthreads();
         const int ncls = M - c0 < kProjTiles * 16 ? M - c0 : kProjTiles * 16;
         for (int node = 0; node < 16; ++node) {
