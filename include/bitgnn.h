@@ -108,8 +108,9 @@ int bitgnn_ctx_set_tuning(bitgnn_ctx *ctx, int32_t cb_nodes, int32_t part_len,
                           int32_t min_avg_degree);
 
 /* Forces one of the two BMM kernels (tests, A/B measurements); BITGNN_BGEMM_MFMA still
- * falls back to the VALU kernel for shapes whose weights do not fit the matrix-core
- * kernel's LDS.  Results never depend on the choice.  Default: BITGNN_BGEMM_AUTO. */
+ * falls back to the VALU kernel for shapes the matrix-core kernel does not take (rows of
+ * more than 16 words; it runs wide outputs in column chunks whose widened weights fit its
+ * LDS).  Results never depend on the choice.  Default: BITGNN_BGEMM_AUTO. */
 int bitgnn_ctx_set_bgemm_path(bitgnn_ctx *ctx, int path);
 /* Which kernel bitgnn_bgemm launches for n rows of kwords 64-bit words against M weight
  * rows under the context's current setting: *kernel <- BITGNN_BGEMM_VALU or _MFMA.  Host

@@ -9,7 +9,8 @@
 // gfx950 mapping
 //  - the weights, widened once per call to bytes (row stride K' + 16 so that the 16-byte
 //    operand reads of 16 columns fall into different LDS bank groups), stay in LDS for the
-//    whole life of a persistent workgroup (hence the limit M' (K' + 16) <= 144 KB);
+//    whole life of a persistent workgroup (M' (K' + 16) <= 144 KB: wider outputs run as
+//    column chunks of whole 64-bit output words, one launch each);
 //  - a wavefront owns 32 node rows (two operands, widened from their packed words with
 //    three VALU ops per four bytes) and walks column groups of 128: 16 accumulators of
 //    16x16, every weight operand read from LDS feeds two MFMAs;
@@ -76,7 +77,7 @@ __device__ __forceinline__ v4i widen16(uint32_t bits)
     return r;
 }
 
-// KS = 64-bit words of a packed row held in registers (K <= 64 KS; 2, 4 or 8).
+// KS = 64-bit words of a packed row held in registers (K <= 64 KS; 2, 4, 8 or 16).
 template <int EPI, int KS>
 __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
     const uint64_t *__restrict__ xbits, int64_t n, int64_t x_stride, int32_t K, int32_t ksteps,
@@ -225,11 +226,21 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
         }
     };
 
+    int64_t panel = blockIdx.x;
+    const int64_t step = gridDim.x;
+    if (KS > 8) {
+        // rows of 16 words: one register set (a second one would spill); a panel's products
+        // take long enough here that the other wavefront of the SIMD covers the loads
+        uint64_t a0[KS], a1[KS];
+        for (; panel * kMfPanel < n; panel += step) { // uniform over the workgroup
+            load_rows(panel, a0, a1);
+            compute(panel, a0, a1);
+        }
+        return;
+    }
     // two register sets: the rows of the next panel are requested before the current
     // panel is computed
     uint64_t a0[KS], a1[KS], b0[KS], b1[KS];
-    int64_t panel = blockIdx.x;
-    const int64_t step = gridDim.x;
     load_rows(panel, a0, a1);
     for (;;) {
         load_rows(panel + step, b0, b1);
@@ -247,23 +258,38 @@ __global__ __launch_bounds__(kMfWaves * 64) void bgemm_mfma_kernel(
 
 } // namespace
 
-// Whether the matrix-core kernel takes this shape: weights resident in LDS, enough work to
-// be compute-bound (small M or K leave the VALU kernel at the memory bound anyway).
+// Output columns per launch: all of them when the widened weights fit in LDS, else the
+// largest multiple of 64 (whole output words) that does; 0 = the shape does not fit at all.
+static int32_t mf_chunk(int64_t Kp, int64_t Mp)
+{
+    const int64_t row = Kp + kMfPad + 8; // widened weights + column constants, per column
+    if (Mp * row <= (int64_t)kMfLdsLimit)
+        return (int32_t)Mp;
+    return (int32_t)((int64_t)kMfLdsLimit / row / 64 * 64);
+}
+
+// Whether the matrix-core kernel takes this shape: weights (or a column chunk of them)
+// resident in LDS, enough work to be compute-bound (small M or K leave the VALU kernel at the
+// memory bound anyway).
 bool bg_bgemm_mfma_applies(const bitgnn_ctx *ctx, int64_t n, int32_t kwords, int32_t M)
 {
     if (ctx->bgemm_path == 1)
         return false;
     const int64_t Kp = (int64_t)kwords * 64, Mp = ((int64_t)M + 15) / 16 * 16;
-    // rows are held in 8 registers; weights and column constants in LDS
-    if (Kp > 512 || (size_t)(Mp * (Kp + kMfPad + 8)) > kMfLdsLimit)
+    // rows are held in registers (up to 16 words); weights and column constants in LDS
+    const int32_t chunk = mf_chunk(Kp, Mp);
+    if (Kp > 1024 || (chunk < Mp && chunk < 64))
         return false;
     if (ctx->bgemm_path == 2)
         return true;
     // measured on MI355X: the fixed cost (widening the weights, one LDS copy of them per
-    // workgroup: 11-22 us whatever n) is repaid from 40-70 thousand rows on, depending on
-    // the shape (K x M = 512 x 256: level at 70 K; 128 x 128: from 20 K; 256 x 40: only
-    // beyond 100 K); 1.4x - 2.4x faster for large n
-    return n >= 65536;
+    // workgroup: 11-22 us whatever n, once per column chunk) is repaid from 40-70 thousand
+    // rows on, depending on the shape (K x M = 512 x 256: level at 70 K; 128 x 128: from
+    // 20 K; 256 x 40: only beyond 100 K); 1.4x - 2.4x faster for large n.  Rows of more
+    // than 8 words and outputs in column chunks pay that cost per chunk and load rows without
+    // a second register set: level with the VALU kernel at 89 K rows (1000 x 256: 79 against
+    // 83 us), 1.4x at 200 K, 1.9x at 500 K, 3x at 2.4 M rows
+    return n >= ((Kp > 512 || chunk < Mp) ? 131072 : 65536);
 }
 
 int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, int64_t n,
@@ -271,26 +297,37 @@ int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, 
                          int32_t M, int64_t w_stride, int epilogue, const int32_t *T,
                          const float *alpha, void *out, int64_t out_stride)
 {
-    const int32_t ldw = kwords * 64 + kMfPad, Mp = (M + 15) / 16 * 16;
-    const size_t w8_bytes = (size_t)Mp * ldw;
-    const size_t lds_bytes = w8_bytes + (size_t)Mp * 8; // + column constants
-    BG_REQUIRE(ctx, w8_bytes + (size_t)Mp * 4 <= kBgemmScratchBytes, BITGNN_ERR_UNSUPPORTED,
-               "bitgnn_bgemm: weights too large for the matrix-core kernel's scratch");
-    uint8_t *w8 = (uint8_t *)ctx->bgemm_ws;
-    int32_t *pw = (int32_t *)(w8 + w8_bytes);
-    bgemm_widen_w_kernel<<<Mp, 256, 0, s>>>((const uint32_t *)wbits, w_stride * 2, kwords * 64, M,
-                                            ldw, w8, pw);
-    BG_LAUNCH_CHECK(ctx, "bgemm_widen_w");
+    const int32_t ldw = kwords * 64 + kMfPad;
+    const int32_t chunk = mf_chunk((int64_t)kwords * 64, ((int64_t)M + 15) / 16 * 16);
+    BG_REQUIRE(ctx, chunk > 0 && (chunk >= 64 || chunk >= M) && kwords <= 16, BITGNN_ERR_UNSUPPORTED,
+               "bitgnn_bgemm: shape too large for the matrix-core kernel");
     const int64_t panels = (n + kMfPanel - 1) / kMfPanel;
     const int64_t cus = ctx->n_cus > 0 ? ctx->n_cus : 256;
     const unsigned grid = (unsigned)(panels < cus ? panels : cus);
+    // Column chunks run one after the other on the stream and share the widening scratch: a
+    // chunk's launches are ordered behind the previous chunk's kernel, which has read it.
+    for (int32_t c0 = 0; c0 < M; c0 += chunk) {
+        const int32_t Mc = M - c0 < chunk ? M - c0 : chunk, Mp = (Mc + 15) / 16 * 16;
+        const size_t w8_bytes = (size_t)Mp * ldw;
+        const size_t lds_bytes = w8_bytes + (size_t)Mp * 8; // + column constants
+        BG_REQUIRE(ctx, w8_bytes + (size_t)Mp * 4 <= kBgemmScratchBytes, BITGNN_ERR_UNSUPPORTED,
+                   "bitgnn_bgemm: weights too large for the matrix-core kernel's scratch");
+        uint8_t *w8 = (uint8_t *)ctx->bgemm_ws;
+        int32_t *pw = (int32_t *)(w8 + w8_bytes);
+        bgemm_widen_w_kernel<<<Mp, 256, 0, s>>>((const uint32_t *)(wbits + (int64_t)c0 * w_stride),
+                                                w_stride * 2, kwords * 64, Mc, ldw, w8, pw);
+        BG_LAUNCH_CHECK(ctx, "bgemm_widen_w");
+        const int32_t *Tc = T ? T + c0 : nullptr;
+        const float *ac = alpha ? alpha + c0 : nullptr;
+        void *oc = epilogue == BITGNN_EPI_THRESH_BITS ? (void *)((uint64_t *)out + c0 / 64)
+                                                      : (void *)((int32_t *)out + c0);
 #define BG_MFMA_KS(E, KS)                                                                         \
     do {                                                                                          \
         BG_HIP(ctx, hipFuncSetAttribute((const void *)bgemm_mfma_kernel<E, KS>,                   \
                                         hipFuncAttributeMaxDynamicSharedMemorySize,               \
                                         (int)lds_bytes));                                         \
         bgemm_mfma_kernel<E, KS><<<grid, kMfWaves * 64, lds_bytes, s>>>(                          \
-            xbits, n, x_stride, K, kwords, (const uint4 *)w8, ldw, pw, M, Mp, T, alpha, out,      \
+            xbits, n, x_stride, K, kwords, (const uint4 *)w8, ldw, pw, Mc, Mp, Tc, ac, oc,        \
             out_stride);                                                                          \
     } while (0)
 #define BG_MFMA(E)                                                                                \
@@ -299,16 +336,19 @@ int bg_launch_bgemm_mfma(bitgnn_ctx *ctx, hipStream_t s, const uint64_t *xbits, 
             BG_MFMA_KS(E, 2);                                                                     \
         else if (kwords <= 4)                                                                     \
             BG_MFMA_KS(E, 4);                                                                     \
-        else                                                                                      \
+        else if (kwords <= 8)                                                                     \
             BG_MFMA_KS(E, 8);                                                                     \
+        else                                                                                      \
+            BG_MFMA_KS(E, 16);                                                                    \
     } while (0)
-    switch (epilogue) {
-    case BITGNN_EPI_THRESH_BITS: BG_MFMA(BITGNN_EPI_THRESH_BITS); break;
-    case BITGNN_EPI_RAW_I32: BG_MFMA(BITGNN_EPI_RAW_I32); break;
-    default: BG_MFMA(BITGNN_EPI_SCALE_F32); break;
-    }
+        switch (epilogue) {
+        case BITGNN_EPI_THRESH_BITS: BG_MFMA(BITGNN_EPI_THRESH_BITS); break;
+        case BITGNN_EPI_RAW_I32: BG_MFMA(BITGNN_EPI_RAW_I32); break;
+        default: BG_MFMA(BITGNN_EPI_SCALE_F32); break;
+        }
 #undef BG_MFMA_KS
 #undef BG_MFMA
-    BG_LAUNCH_CHECK(ctx, "bgemm_mfma");
+        BG_LAUNCH_CHECK(ctx, "bgemm_mfma");
+    }
     return BITGNN_OK;
 }

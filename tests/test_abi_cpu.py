@@ -153,6 +153,9 @@ def test_workspace_and_bgemm_path_calls(vctx):
     assert B.ctx_bgemm_kernel(vctx, 1000, 2, 128) == B.BGEMM_VALU
     assert B.ctx_bgemm_kernel(vctx, 232965, 2, 128) == B.BGEMM_MFMA
     assert B.ctx_bgemm_kernel(vctx, 232965, 32, 128) == B.BGEMM_VALU     # K = 2048: not in LDS
+    assert B.ctx_bgemm_kernel(vctx, 232965, 16, 256) == B.BGEMM_MFMA     # K = 1024: column chunks,
+    assert B.ctx_bgemm_kernel(vctx, 89250, 16, 256) == B.BGEMM_VALU      # from 131,072 rows on
+    assert B.ctx_bgemm_kernel(vctx, 89250, 8, 7) == B.BGEMM_MFMA         # 16 padded columns fit
     B.ctx_set_bgemm_path(vctx, B.BGEMM_VALU)
     assert B.ctx_bgemm_kernel(vctx, 232965, 2, 128) == B.BGEMM_VALU
     B.ctx_set_bgemm_path(vctx, B.BGEMM_MFMA)

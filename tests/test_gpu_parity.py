@@ -182,7 +182,9 @@ def _pack_host(v):
 @pytest.mark.parametrize("n,K,M", [
     (1, 1, 1), (5, 63, 7), (129, 64, 64), (300, 65, 65), (1000, 100, 41), (777, 602, 128),
     (500, 1433, 64), (2048, 512, 256), (100, 1000, 47), (4099, 128, 40), (33, 2100, 130),
-    (5000, 200, 256), (6000, 512, 47), (4500, 64, 33), (300, 96, 528)])
+    (5000, 200, 256), (6000, 512, 47), (4500, 64, 33), (300, 96, 528),
+    # matrix-core kernel in column chunks: 2 x 128, 128 + 128 + 44, 256 + 256 + 88
+    (1500, 1000, 256), (700, 1000, 300), (400, 512, 600)])
 def test_bgemm_three_epilogues(B, gemm_ctx, n, K, M):
     ctx = gemm_ctx
     r = np.random.default_rng(K * 1000 + M)
