@@ -36,7 +36,7 @@ def source_stamp():
     profiles/ were taken with: counters of other code are not this run's."""
     import hashlib
     h = hashlib.sha1()
-    for f in ("bspmm.hip", "adj_blocked.hip", "bgemm.hip", "bgemm_mfma.hip"):
+    for f in ("bspmm.hip", "adj_blocked.hip", "bgemm.hip", "bgemm_mfma.hip", "pack.hip"):
         h.update(open(os.path.join(ROOT, "paper_2305_02522_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:12]
 
@@ -459,7 +459,7 @@ def main():
         return {"bspmm": "bspmm_blk_kernel" if took_blocked else "bspmm_kernel",
                 "out_layer": "bspmm_blk_kernel" if lab in agg_kernel_ms else "spmm_i32_kernel",
                 "bgemm_f32": "bgemm_f32_kernel", "gcn2_fused": "gcn2_fused_kernel",
-                "pack_f32": "pack_rows_kernel"}[kind]
+                "pack_f32": "pack_rows4_kernel"}[kind]
 
     kernels = {}
     for lab, ts in per_op.items():
