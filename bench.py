@@ -134,6 +134,11 @@ def op_models(wl, nnz, blocked, fused=False, bgemm_kernel=None):
                                       bound="hbm")
             out_b = 4 * n * m if last else 8 * n * w64(m)
             ops[f"L{l}.bgemm"] = bgemm_op(2 * k_in, 2 * kw, m, 16 * kw * (n + m) + out_b)
+    # the same ops priced with CSR's index bytes, whatever format is stored: a measure that
+    # does not move when the stored format shrinks or grows
+    for lab, op in ops.items():
+        if lab.endswith(".bspmm") or lab.endswith(".out_layer"):
+            op["bytes_csr"] = op["bytes"] - idx_bytes + 4 * nnz + 4 * (n + 1)
     return ops
 
 
@@ -506,6 +511,9 @@ def main():
                     unit=unit, frac=frac, avg_launch_us=round(davg * 1e3, 2),
                     call={"avg_us": round(call_avg * 1e3, 2), **fractions(dm, call_avg)},
                     traffic=None)
+    if "bytes_csr" in dm:   # the launch priced at CSR's 4 bytes per non-zero
+        roofline["frac_at_csr_bytes"] = round(
+            dm["bytes_csr"] / launches / (davg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     c = counters.get(kname)
     if c:       # the instantiation whose duration is closest to this run's launches
         v = min(c.values(), key=lambda v: abs(v.get("us", 0.0) - davg * 1e3))

@@ -17,8 +17,9 @@
 //    each touching one or two column blocks; partial counts are merged later.
 //    This bounds the work of one lane, which balances wavefronts on a
 //    power-law graph;
-//  - parts are ordered by (first block, last block, length); 64 consecutive
-//    parts form a slice (one wavefront, one part per lane), 16 slices a
+//  - parts are ordered by (first block, last block, entries in the first block,
+//    entries in the second block), so that the lanes of a tile have similar
+//    step counts; 64 consecutive parts form a slice (one wavefront, one part per lane), 16 slices a
 //    workgroup.  For every (slice, block) tile the ids are stored lane-
 //    interleaved in groups of kGroupSteps steps: group g holds
 //    idx16[(g*64+lane)*kGroupSteps+k], padded with ids cbn .. cbn+15, which address
@@ -114,7 +115,35 @@ __global__ void vrow_kernel(const uint64_t *__restrict__ skeys, const uint32_t *
         v_beg[v] = b;
         v_end[v] = e;
         v_slot[v] = s | (np == 1 ? 0x80000000u : 0u); // bit 31: the row's only part
-        vkeys[v] = (lo << 52) | (hi << 40) | ((uint64_t)(1023u - len) << 30) | v;
+        // Entries in the part's first two blocks (its heaviest: columns are in degree
+        // order).  The parts of a slice share their tiles' step counts (the longest lane's),
+        // so within a block range they are ordered by these two counts rather than by
+        // length: on a Reddit-shaped graph 12 % fewer stored ids than ordering by length.
+        uint32_t c0 = 0, c1 = 0;
+        if (len) {
+            uint32_t a = b, z = e; // first entry with column >= (lo + 1) cbn
+            const uint64_t lim0 = (lo + 1) * (uint32_t)cbn, lim1 = lim0 + (uint32_t)cbn;
+            while (a < z) {
+                const uint32_t m = (a + z) >> 1;
+                if ((skeys[m] & mask) < lim0)
+                    a = m + 1;
+                else
+                    z = m;
+            }
+            c0 = a - b;
+            z = e; // first entry with column >= (lo + 2) cbn, searched from there on
+            while (a < z) {
+                const uint32_t m = (a + z) >> 1;
+                if ((skeys[m] & mask) < lim1)
+                    a = m + 1;
+                else
+                    z = m;
+            }
+            c1 = a - b - c0;
+        }
+        const uint64_t sig =
+            ((uint64_t)(31u - min(c0 >> 3, 31u)) << 5) | (31u - min(c1 >> 2, 31u));
+        vkeys[v] = (lo << 52) | (hi << 40) | (sig << 30) | v;
     }
 }
 
