@@ -316,6 +316,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=1 << 30,
                     help="rows of the workload the CPU oracle is timed on (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the leg that replays the step from a captured HIP graph")
     ap.add_argument("--cold-steps", type=int, default=5,
                     help="steps of the cache-flushed leg (1.25 GB swept through the caches "
                     "before each; reported beside the steady-state numbers; 0 = skip)")
@@ -522,6 +524,31 @@ def main():
         roofline["traffic_frac_of_hbm_peak"] = round(
             v["hbm_MB"] * 1e6 / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if v.get("us") else None
 
+    # HIP-graph leg: the same step captured once and replayed K times (no instrumentation
+    # inside): what the launches and the event records of the timed region cost
+    graph_leg = None
+    if not args.no_graph:
+        try:
+            logits_ref = model.logits.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run_step()
+            for _ in range(2):
+                g.replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            g_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+            graph_leg = {"ms_per_step": round(g_ms, 4),
+                         "Gbit_edge_ops_per_s": round(total_work / g_ms / 1e6, 1),
+                         "logits_equal_eager": bool(torch.equal(logits_ref, model.logits))}
+            del g
+        except Exception as e:      # capture is an extra: report, do not fail the bench
+            graph_leg = {"error": str(e)[:200]}
+            torch.cuda.synchronize()
+
     # cache-flushed leg: the same step with > 1 GB swept through the caches before every
     # step (the 256 MB Infinity Cache and the L2 then hold none of the operands)
     cold = None
@@ -561,6 +588,8 @@ def main():
                    "aggregation_format": blocked},
         "kernels": kernels, "roofline": roofline,
     }
+    if graph_leg:
+        result["graph_replay"] = graph_leg
     if cold:
         result["cache_flushed"] = cold
     if not args.no_cpu_baseline:
