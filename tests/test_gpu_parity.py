@@ -1032,3 +1032,32 @@ def test_gcn2_fused_rejects_what_it_cannot_run(B, ctx):
 @pytest.mark.parametrize("cfg", [2, 3])
 def test_model_full_size(B, ctx, cfg):
     _check_model(B, ctx, W.make_workload(cfg))
+
+
+@pytest.mark.parametrize("cfg,kw", [(2, {"n": 1 << 13}), (3, {"n": 20000}),
+                                    (4, {"n": 6000, "mean_deg": 120.0})])
+def test_model_replayed_from_a_hip_graph(B, ctx, cfg, kw):
+    """BinaryGNN.capture: the layer calls of a whole model recorded once, replayed on new
+    features with the program's own eager work and synchronizations between the replays;
+    every replay gives the oracle's logits and the eager run's bits."""
+    wl = W.make_workload(cfg, **kw)
+    src, dst = dev(wl.src), dev(wl.dst)
+    adj = B.adj_build(ctx, src, dst, len(wl.src), wl.n, wl.adj_flags)
+    model = B.BinaryGNN(ctx, wl.model, adj, wl.dims, wl.layers)
+    rp, col = orc.adjacency(wl.src, wl.dst, wl.n, wl.adj_flags)
+    x = dev(wl.x.astype(np.float32))
+    g = model.capture(x)
+    r = np.random.default_rng(cfg)
+    for rep in range(3):
+        xs = (wl.x * (1.0 if rep == 0 else -1.0) +
+              (0.0 if rep < 2 else r.normal(0, 1, wl.x.shape))).astype(np.float32)
+        x.copy_(dev(xs))                        # new contents at the captured address
+        model.logits.fill_(-7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        got = model.logits.cpu().numpy().copy()
+        ref = orc.forward(wl.model, rp, col, orc.bin_f32(xs), wl.layers)
+        assert rel_close(got, ref), f"replay {rep}"
+        eager = model.forward(x).cpu().numpy()  # eager work between the replays
+        assert np.array_equal(got, eager), f"replay {rep} against the eager run"
+    adj.close()
