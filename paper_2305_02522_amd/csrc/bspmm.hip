@@ -64,10 +64,31 @@ __device__ __forceinline__ void seed_entry(int idx, const int32_t *__restrict__ 
     table[idx] = word;
 }
 
-__global__ void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C, int32_t W32, int P,
-                                  uint32_t *__restrict__ table)
+// One half wavefront per table word, one lane per channel: the word is the vote of the 32
+// lanes (a thread per word walked its 32 thresholds one after the other: 6 us for a table
+// of a few hundred words, a quarter of a small graph's aggregation).
+__global__ __launch_bounds__(256) void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C,
+                                                         int32_t W32, int P,
+                                                         uint32_t *__restrict__ table)
 {
-    seed_entry(blockIdx.x * blockDim.x + threadIdx.x, T, C, W32, P, table);
+    const int idx = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 5);
+    const int b = threadIdx.x & 31;
+    const bool valid = idx < 2 * P * W32;
+    const int w = valid ? idx % W32 : 0;
+    const int p = valid ? (idx / W32) % P : 0;
+    const int e = valid ? idx / (W32 * P) : 0;
+    const int c = 32 * w + b;
+    bool bit = false;
+    if (valid && c < C) {
+        const int64_t lim = 1ll << (P - 2);
+        int64_t t = ((int64_t)T[c] + e + 1) >> 1; // floor
+        t = t > lim ? lim : (t < -lim ? -lim : t);
+        const uint64_t off = (uint64_t)((1ll << (P - 1)) - t);
+        bit = (off >> p) & 1u;
+    }
+    const uint64_t vote = __ballot(bit);
+    if (valid && b == 0)
+        table[idx] = (uint32_t)((threadIdx.x & 32) ? vote >> 32 : vote);
 }
 
 // Epilogue of one (node, 32-channel word): `acc` holds the bit-sliced count (plus
@@ -1364,7 +1385,8 @@ static int launch_seeds(bitgnn_ctx *ctx, hipStream_t s, int epilogue, const int3
     const int entries = 2 * P * W32;
     BG_REQUIRE(ctx, (size_t)entries <= ctx->sc->seed_table_words, BITGNN_ERR_UNSUPPORTED,
                "bitgnn_bspmm: seed table too small");
-    bspmm_seed_kernel<<<(entries + 127) / 128, 128, 0, s>>>(T, C, W32, P, ctx->sc->seed_table);
+    bspmm_seed_kernel<<<(entries * 32 + 255) / 256, 256, 0, s>>>(T, C, W32, P,
+                                                              ctx->sc->seed_table);
     BG_LAUNCH_CHECK(ctx, "bspmm_seed");
     *seeds = ctx->sc->seed_table;
     return BITGNN_OK;
