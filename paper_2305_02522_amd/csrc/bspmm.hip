@@ -435,14 +435,16 @@ __global__ __launch_bounds__(kBlock) void spmm_i32_wide_kernel(
                     acc += z[u];
         }
     }
-    // lanes of slot 0 collect the other slots' sums
-    for (int kq = 1; kq < Q; ++kq) {
+    // the slots' sums are folded in halves until slot 0 holds the total
+    for (int active = Q; active > 1;) {
+        const int half = (active + 1) / 2;
 #pragma unroll
         for (int i = 0; i < VW; ++i) {
-            const int32_t other = __shfl(acc[i], lane + kq * LR, 64);
-            if (q == 0)
+            const int32_t other = __shfl(acc[i], lane + half * LR, 64);
+            if (q + half < active)
                 acc[i] += other;
         }
+        active = half;
     }
     if (q != 0)
         return;
