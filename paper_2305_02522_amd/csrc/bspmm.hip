@@ -42,38 +42,16 @@ __device__ __forceinline__ void csa(uint32_t &acc, uint32_t b, uint32_t c, uint3
 
 // Seeds of the vertical counters: table[(e*P + p)*W32 + w] bit c' = bit p of
 // (BIAS - t(e, c)), c = 32 w + c', BIAS = 2^(P-1), t clamped to +-2^(P-2).
-__device__ __forceinline__ void seed_entry(int idx, const int32_t *__restrict__ T, int32_t C,
-                                           int32_t W32, int P, uint32_t *__restrict__ table)
-{
-    if (idx >= 2 * P * W32)
-        return;
-    const int w = idx % W32;
-    const int p = (idx / W32) % P;
-    const int e = idx / (W32 * P);
-    const int64_t lim = 1ll << (P - 2);
-    uint32_t word = 0;
-    for (int b = 0; b < 32; ++b) {
-        const int c = 32 * w + b;
-        if (c >= C)
-            break;
-        int64_t t = ((int64_t)T[c] + e + 1) >> 1; // floor
-        t = t > lim ? lim : (t < -lim ? -lim : t);
-        const uint64_t off = (uint64_t)((1ll << (P - 1)) - t);
-        word |= (uint32_t)((off >> p) & 1u) << b;
-    }
-    table[idx] = word;
-}
-
 // One half wavefront per table word, one lane per channel: the word is the vote of the 32
 // lanes (a thread per word walked its 32 thresholds one after the other: 6 us for a table
-// of a few hundred words, a quarter of a small graph's aggregation).
-__global__ __launch_bounds__(256) void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C,
-                                                         int32_t W32, int P,
-                                                         uint32_t *__restrict__ table)
+// of a few hundred words, a quarter of a small graph's aggregation).  Every lane of the
+// wavefront must call; `t` is the thread's index among the threads that build the table.
+__device__ __forceinline__ void seed_word_vote(int t, int n_words, const int32_t *__restrict__ T,
+                                               int32_t C, int32_t W32, int P,
+                                               uint32_t *__restrict__ table)
 {
-    const int idx = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 5);
-    const int b = threadIdx.x & 31;
-    const bool valid = idx < 2 * P * W32;
+    const int idx = t >> 5, b = t & 31;
+    const bool valid = t >= 0 && idx < n_words;
     const int w = valid ? idx % W32 : 0;
     const int p = valid ? (idx / W32) % P : 0;
     const int e = valid ? idx / (W32 * P) : 0;
@@ -81,14 +59,21 @@ __global__ __launch_bounds__(256) void bspmm_seed_kernel(const int32_t *__restri
     bool bit = false;
     if (valid && c < C) {
         const int64_t lim = 1ll << (P - 2);
-        int64_t t = ((int64_t)T[c] + e + 1) >> 1; // floor
-        t = t > lim ? lim : (t < -lim ? -lim : t);
-        const uint64_t off = (uint64_t)((1ll << (P - 1)) - t);
+        int64_t th = ((int64_t)T[c] + e + 1) >> 1; // floor
+        th = th > lim ? lim : (th < -lim ? -lim : th);
+        const uint64_t off = (uint64_t)((1ll << (P - 1)) - th);
         bit = (off >> p) & 1u;
     }
     const uint64_t vote = __ballot(bit);
     if (valid && b == 0)
-        table[idx] = (uint32_t)((threadIdx.x & 32) ? vote >> 32 : vote);
+        table[idx] = (uint32_t)((t & 32) ? vote >> 32 : vote);
+}
+
+__global__ __launch_bounds__(256) void bspmm_seed_kernel(const int32_t *__restrict__ T, int32_t C,
+                                                         int32_t W32, int P,
+                                                         uint32_t *__restrict__ table)
+{
+    seed_word_vote((int)(blockIdx.x * blockDim.x + threadIdx.x), 2 * P * W32, T, C, W32, P, table);
 }
 
 // Epilogue of one (node, 32-channel word): `acc` holds the bit-sliced count (plus
@@ -638,11 +623,14 @@ __global__ __launch_bounds__(256) void blk_permute_kernel(
     if (blockIdx.x >= permute_blocks) { // workgroup-uniform: the set-up work's own workgroups
         const int vb = (int)(blockIdx.x - permute_blocks);
         if (aux.kind == 1) {
-            const int e = vb * 256 + (int)threadIdx.x, n_merge = 2 * aux.P * aux.W32;
-            if (e < n_merge)
-                seed_entry(e, aux.T, aux.C, aux.W32, aux.P, aux.table);
+            // 32 threads per table word: first the merge's table, then (wavefronts of
+            // their own: the word counts are even) the finished rows' table
+            const int t = vb * 256 + (int)threadIdx.x, n_merge = 2 * aux.P * aux.W32;
+            if (t < n_merge * 32) // uniform over a wavefront
+                seed_word_vote(t, n_merge, aux.T, aux.C, aux.W32, aux.P, aux.table);
             else if (aux.PF)
-                seed_entry(e - n_merge, aux.T, aux.C, aux.W32, aux.PF, aux.table_fin);
+                seed_word_vote(t - n_merge * 32, 2 * aux.PF * aux.W32, aux.T, aux.C, aux.W32,
+                               aux.PF, aux.table_fin);
         } else if (aux.kind == 2)
             project_weights_entry(vb % aux.Mpad, vb / aux.Mpad, (int)threadIdx.x, aux.w32,
                                   aux.w_stride32, aux.K, aux.M, aux.Mpad, aux.w8, aux.wsum);
@@ -1371,7 +1359,7 @@ static void launch_permute(hipStream_t s, const bitgnn_adj *adj, const uint32_t 
     const unsigned pb = (unsigned)((adj->n + 255) / 256);
     unsigned extra = 0;
     if (aux.kind == 1)
-        extra = (unsigned)((2 * (aux.P + aux.PF) * aux.W32 + 255) / 256);
+        extra = (unsigned)((2 * (aux.P + aux.PF) * aux.W32 * 32 + 255) / 256);
     else if (aux.kind == 2)
         extra = (unsigned)(aux.Mpad * aux.nwin);
     blk_permute_kernel<<<pb + extra, 256, 0, s>>>(h32, h_stride32, adj->order, (uint32_t)adj->n, w0,
