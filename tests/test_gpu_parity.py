@@ -71,7 +71,11 @@ def rel_close(got, ref, tol=1e-5):
 # ------------------------------------------------------------------ a1: pack
 @pytest.mark.parametrize("n,K,pad_ld,pad_out", [
     (1, 1, 0, 0), (3, 63, 0, 0), (5, 64, 3, 1), (130, 65, 0, 0), (257, 100, 4, 2),
-    (1000, 602, 0, 0), (2708, 1433, 0, 0), (64, 4096, 0, 0), (70001, 128, 0, 0)])
+    (1000, 602, 0, 0), (2708, 1433, 0, 0), (64, 4096, 0, 0), (70001, 128, 0, 0),
+    # rows of fewer than 4 elements (one element per lane), rows that end inside a lane's 4
+    # elements (the load is moved back and the nibble shifted), rows at odd element offsets
+    (7, 2, 1, 0), (9, 3, 0, 1), (33, 4, 1, 0), (33, 5, 0, 0), (100, 6, 3, 0), (100, 7, 0, 0),
+    (257, 66, 1, 0), (300, 67, 0, 2), (129, 127, 1, 0), (50, 129, 2, 0), (1025, 191, 5, 0)])
 def test_pack_f32(B, ctx, n, K, pad_ld, pad_out):
     r = np.random.default_rng(n * 7919 + K)
     ldx = K + pad_ld
@@ -96,7 +100,8 @@ def test_pack_f32(B, ctx, n, K, pad_ld, pad_out):
     assert np.array_equal(words_np(out)[:, :kw], orc.to_words(orc.bin_f32(x[:, :K], tau)))
 
 
-@pytest.mark.parametrize("n,K", [(1, 1), (77, 100), (300, 1433), (5000, 64)])
+@pytest.mark.parametrize("n,K", [(1, 1), (77, 100), (300, 1433), (5000, 64), (40, 3), (41, 5),
+                                 (300, 66), (123, 130)])
 def test_pack_i8_and_weights(B, ctx, n, K):
     r = np.random.default_rng(K)
     x = r.integers(-128, 128, size=(n, K), dtype=np.int8)
